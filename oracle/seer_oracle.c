@@ -1,0 +1,257 @@
+/*
+ * CPU oracle for the SeerAttention-R decode hot path.  TEST INFRASTRUCTURE ONLY:
+ * it defines what the GPU library must compute and is called from tests/, the
+ * smoke check and the bench's cpu_baseline leg - never from the product path.
+ * It shares no code, header, table or helper with the HIP library.
+ *
+ * Everything is the plain definition, in fp64, reading the bf16 inputs exactly
+ * (a bf16 value is the upper 16 bits of an IEEE fp32 value):
+ *
+ *   gate score      s_j = sum_c q_gate[c] * k_gate[j][c]      (Eq. 1c, before the
+ *                   softmax; Sec. 3.1 notes that top-k needs no softmax)
+ *   token budget    block budget = token budget / block size, keep the top-k
+ *                   scored blocks (Sec. 3.1), lowest index first among equals
+ *   threshold       S = softmax_j(s_j / sqrt(d_gate)) (Eq. 1c); keep S_j > tau
+ *                   (Sec. 3.1)
+ *   last block      while seqlen is not a multiple of the block size the newest
+ *                   cache entry is stale, so the last block is always kept
+ *                   (Sec. 3.2, Fig. 3)
+ *   sparse decode   softmax(scale * q.K^T) V restricted to the tokens of the
+ *                   selected blocks, one block list shared by the query heads of
+ *                   a kv head; invalid list entries are skipped (Sec. 3.3)
+ *
+ * No blocking, no online rescaling, no split-K: two passes over the selected
+ * tokens (max, then sums), sums taken in index order.
+ *
+ * Pins (tests/test_oracle_pins.py): dense attention computed independently when all
+ * blocks are selected; closed forms for identical keys; needle keys; -inf masking
+ * equivalence; lse partition algebra; brute-force subset enumeration for the top-k;
+ * exact rational arithmetic for the score; softmax invariants for the threshold.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double bf16_value(uint16_t bits) {
+  uint32_t u = (uint32_t)bits << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ gate */
+
+/* Scores of the full blocks of one (sequence, kv head).  kc rows are kc_stride_block
+ * elements apart.  scores[j] for j < nfull. */
+static void gate_scores_group(const uint16_t* qg, const uint16_t* kc, int64_t kc_stride_block,
+                              int dg, int nfull, double* scores) {
+  for (int j = 0; j < nfull; ++j) {
+    const uint16_t* row = kc + (int64_t)j * kc_stride_block;
+    double s = 0.0;
+    for (int c = 0; c < dg; ++c) s += bf16_value(qg[c]) * bf16_value(row[c]);
+    scores[j] = s;
+  }
+}
+
+typedef struct { double s; int j; } scored_t;
+
+/* higher score first; among equal scores the lower block index first */
+static int by_score_then_index(const void* a, const void* b) {
+  const scored_t* x = (const scored_t*)a;
+  const scored_t* y = (const scored_t*)b;
+  if (x->s > y->s) return -1;
+  if (x->s < y->s) return 1;
+  return (x->j > y->j) - (x->j < y->j);
+}
+
+static int by_int(const void* a, const void* b) {
+  int x = *(const int*)a, y = *(const int*)b;
+  return (x > y) - (x < y);
+}
+
+/*
+ * mode 0: token budget.  k = budget_blocks[i] if given, else ceil(budget_tokens / b);
+ *         clamped to [0, min(nb, max_sel)].  With a partial last block, that block takes
+ *         one of the k slots and the other k-1 go to the best full blocks.
+ * mode 1: threshold on the softmax over full blocks; the partial last block is added.
+ * Output per group: ascending block indices, padded with -1 to max_sel; count in nblk.
+ * scores_out (optional, [B,Hkv,nb_max]) receives the raw scores (NaN where not computed).
+ * Returns 0, or -1 when a threshold selection does not fit max_sel.
+ */
+int oracle_gate_select(const uint16_t* q_gate, const uint16_t* kc_cache, int64_t kc_stride_batch,
+                       int64_t kc_stride_head, int64_t kc_stride_block, const int32_t* seqlens, int B,
+                       int Hkv, int Dg, int nb_max, int block_size, int mode, int32_t budget_tokens,
+                       const int32_t* budget_blocks, double threshold, int32_t* block_idx,
+                       int32_t* nblk, int max_sel, double* scores_out) {
+  int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+  for (int i = 0; i < B; ++i) {
+    for (int h = 0; h < Hkv; ++h) {
+      const int64_t grp = (int64_t)i * Hkv + h;
+      int32_t* out = block_idx + grp * max_sel;
+      for (int p = 0; p < max_sel; ++p) out[p] = -1;
+      nblk[grp] = 0;
+      int S = seqlens[i];
+      if (S < 0) S = 0;
+      int nfull = S / block_size;
+      int nb = (S + block_size - 1) / block_size;
+      if (nb > nb_max) { nb = nb_max; if (nfull > nb) nfull = nb; }
+      const int partial = nb > nfull;
+
+      double* scores = (double*)malloc(sizeof(double) * (size_t)(nfull > 0 ? nfull : 1));
+      gate_scores_group(q_gate + grp * Dg, kc_cache + i * kc_stride_batch + h * kc_stride_head,
+                        kc_stride_block, Dg, nfull, scores);
+      if (scores_out) {
+        double* so = scores_out + grp * nb_max;
+        for (int j = 0; j < nb_max; ++j) so[j] = j < nfull ? scores[j] : NAN;
+      }
+
+      int* sel = (int*)malloc(sizeof(int) * (size_t)(nb > 0 ? nb : 1));
+      int n = 0;
+      if (mode == 0) {
+        int64_t k = budget_blocks ? (int64_t)budget_blocks[i]
+                                  : ((int64_t)budget_tokens + block_size - 1) / block_size;
+        if (k < 0) k = 0;
+        if (k > nb) k = nb;
+        if (k > max_sel) k = max_sel;
+        int from_full = (int)k;
+        if (partial && k > 0) from_full = (int)k - 1;
+        if (from_full > nfull) from_full = nfull;
+        scored_t* order = (scored_t*)malloc(sizeof(scored_t) * (size_t)(nfull > 0 ? nfull : 1));
+        for (int j = 0; j < nfull; ++j) { order[j].s = scores[j]; order[j].j = j; }
+        qsort(order, (size_t)nfull, sizeof(scored_t), by_score_then_index);
+        for (int r = 0; r < from_full; ++r) sel[n++] = order[r].j;
+        if (partial && k > 0) sel[n++] = nb - 1;
+        free(order);
+      } else {
+        if (nfull > 0) {
+          const double inv = 1.0 / sqrt((double)Dg);
+          double m = -INFINITY;
+          for (int j = 0; j < nfull; ++j) { double x = scores[j] * inv; if (x > m) m = x; }
+          double Z = 0.0;
+          for (int j = 0; j < nfull; ++j) Z += exp(scores[j] * inv - m);
+          for (int j = 0; j < nfull; ++j) {
+            double Sj = exp(scores[j] * inv - m) / Z;
+            if (Sj > threshold) sel[n++] = j;
+          }
+        }
+        if (partial) sel[n++] = nb - 1;
+      }
+      qsort(sel, (size_t)n, sizeof(int), by_int);
+      if (n > max_sel) {
+#pragma omp atomic write
+        failed = 1;
+        n = max_sel;
+      }
+      for (int p = 0; p < n; ++p) out[p] = sel[p];
+      nblk[grp] = n;
+      free(sel);
+      free(scores);
+    }
+  }
+  return failed ? -1 : 0;
+}
+
+/* ---------------------------------------------------------------- decode */
+
+typedef struct {
+  const uint16_t* k;
+  const uint16_t* v;
+  int64_t stride_seq;   /* elements between sequences (contiguous) or pages (paged) */
+  int64_t stride_head;
+  int64_t stride_token;
+  const int32_t* page_table; /* [B, max_pages] or NULL */
+  int32_t max_pages;
+  int32_t page_size;
+} oracle_kv_t;
+
+static int64_t token_offset(const oracle_kv_t* kv, int i, int hk, int64_t t) {
+  if (kv->page_table) {
+    int64_t page = kv->page_table[(int64_t)i * kv->max_pages + t / kv->page_size];
+    return page * kv->stride_seq + (int64_t)hk * kv->stride_head + (t % kv->page_size) * kv->stride_token;
+  }
+  return (int64_t)i * kv->stride_seq + (int64_t)hk * kv->stride_head + t * kv->stride_token;
+}
+
+/*
+ * Attention of every query head over the tokens of the listed blocks.
+ * block_idx == NULL: all blocks (dense).  Otherwise the first min(nblk, max_sel) entries of
+ * the group's list are used; entries < 0 or >= ceil(S/b) are skipped.
+ * out [B,Hq,d] fp64, lse [B,Hq] fp64 (natural log of sum exp(scale*q.k)); an empty token
+ * set gives out = 0 and lse = -inf.
+ * group_filter (optional, [B*Hkv] bytes): groups with 0 are left untouched.
+ */
+int oracle_sparse_decode(const uint16_t* q, const oracle_kv_t* kv, const int32_t* seqlens,
+                         const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int Hq,
+                         int Hkv, int d, int block_size, float scale, double* out, double* lse,
+                         const uint8_t* group_filter) {
+  if (Hkv <= 0 || Hq % Hkv) return -1;
+  const int g = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+  for (int i = 0; i < B; ++i) {
+    for (int hk = 0; hk < Hkv; ++hk) {
+      const int64_t grp = (int64_t)i * Hkv + hk;
+      if (group_filter && !group_filter[grp]) continue;
+      int S = seqlens[i];
+      if (S < 0) S = 0;
+      const int nb = (S + block_size - 1) / block_size;
+
+      /* token list of the group */
+      int nlist = block_idx ? nblk[grp] : nb;
+      if (nlist < 0) nlist = 0;
+      if (block_idx && nlist > max_sel) nlist = max_sel;
+      int64_t cap = (int64_t)nlist * block_size;
+      int64_t* toks = (int64_t*)malloc(sizeof(int64_t) * (size_t)(cap > 0 ? cap : 1));
+      int64_t nt = 0;
+      for (int p = 0; p < nlist; ++p) {
+        int j = block_idx ? block_idx[grp * max_sel + p] : p;
+        if (j < 0 || j >= nb) continue;
+        int64_t t0 = (int64_t)j * block_size;
+        int64_t t1 = t0 + block_size;
+        if (t1 > S) t1 = S;
+        for (int64_t t = t0; t < t1; ++t) toks[nt++] = t;
+      }
+
+      double* x = (double*)malloc(sizeof(double) * (size_t)(nt > 0 ? nt : 1));
+      for (int hh = 0; hh < g; ++hh) {
+        const int h = hk * g + hh;
+        const uint16_t* qrow = q + ((int64_t)i * Hq + h) * d;
+        double* orow = out + ((int64_t)i * Hq + h) * d;
+        for (int c = 0; c < d; ++c) orow[c] = 0.0;
+        if (nt == 0) { lse[(int64_t)i * Hq + h] = -INFINITY; continue; }
+        double m = -INFINITY;
+        for (int64_t r = 0; r < nt; ++r) {
+          const uint16_t* krow = kv->k + token_offset(kv, i, hk, toks[r]);
+          double dot = 0.0;
+          for (int c = 0; c < d; ++c) dot += bf16_value(qrow[c]) * bf16_value(krow[c]);
+          x[r] = (double)scale * dot;
+          if (x[r] > m) m = x[r];
+        }
+        double Z = 0.0;
+        for (int64_t r = 0; r < nt; ++r) Z += exp(x[r] - m);
+        const double l = m + log(Z);
+        for (int64_t r = 0; r < nt; ++r) {
+          const double p = exp(x[r] - l);
+          const uint16_t* vrow = kv->v + token_offset(kv, i, hk, toks[r]);
+          for (int c = 0; c < d; ++c) orow[c] += p * bf16_value(vrow[c]);
+        }
+        lse[(int64_t)i * Hq + h] = l;
+      }
+      free(x);
+      free(toks);
+    }
+  }
+  return 0;
+}
