@@ -1,0 +1,185 @@
+/*
+ * seer.h - C ABI of the SeerAttention-R decode hot path for AMD MI355X (gfx950).
+ *
+ * Two operations, both shared by all query heads of a kv head (GQA-shared sparsity,
+ * Sec. 2.2 "Aggregation of Query Heads"):
+ *
+ *   seer_gate_select    AttnGate block selection: score of every cached block against the
+ *                       K Compression Cache (Eq. 1c, Sec. 3.2), then token-budget top-k or
+ *                       threshold selection (Sec. 3.1), last block forced while it is
+ *                       partial (Sec. 3.2, Fig. 3).
+ *   seer_sparse_decode  block-sparse flash-decoding: attention of the new token over the
+ *                       selected KV blocks only, split over the selected-block list and
+ *                       merged by log-sum-exp (Sec. 3.3).
+ *   seer_dense_decode   the same kernels walking every block (the dense flash-decode the
+ *                       sparse kernel is compared with, Sec. 4.4).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless marked "host".  The caller owns all
+ *     buffers; the library never allocates, frees or synchronises.  Scratch memory is a
+ *     caller-supplied workspace sized by the *_workspace_bytes queries.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
+ *     stream) and the calls return immediately.
+ *   - bf16 data is the upper half of an IEEE fp32.  K/V/q/kc base pointers are 16-byte
+ *     aligned and all strides are multiples of 8 elements; the innermost (feature)
+ *     dimension is contiguous.
+ *   - Return value: SEER_OK or a negative seer_status.  Argument errors that the host can
+ *     see (NULL pointers, unsupported sizes, short workspace) are reported before anything
+ *     is launched.  Data-dependent conditions on the device are defined behaviour, not
+ *     errors (see each call).
+ *   - Supported sizes: head dim d = 128, gate dim Dg = 128, block_size in {16, 32, 64, 128}
+ *     ... of which 64 and 128 are the tuned ones, group size Hq/Hkv in 1..8.
+ */
+#ifndef SEER_H
+#define SEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum seer_status {
+  SEER_OK = 0,
+  SEER_ERR_NULL = -1,        /* a required pointer is NULL                          */
+  SEER_ERR_SHAPE = -2,       /* a size is non-positive or sizes are inconsistent    */
+  SEER_ERR_UNSUPPORTED = -3, /* valid but not implemented (d, Dg, block size, g)    */
+  SEER_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small          */
+  SEER_ERR_CAPACITY = -5,    /* max_sel cannot hold the selection that was asked for */
+  SEER_ERR_HIP = -6          /* a HIP runtime call failed (launch error)            */
+} seer_status;
+
+typedef enum seer_select_mode {
+  SEER_SELECT_TOPK = 0,      /* token budget -> block budget -> top-k (Sec. 3.1)    */
+  SEER_SELECT_THRESHOLD = 1  /* softmaxed gate score > threshold (Sec. 3.1)         */
+} seer_select_mode;
+
+typedef enum seer_dtype { SEER_BF16 = 0, SEER_F32 = 1 } seer_dtype;
+
+/*
+ * Addressing of the bf16 KV cache.  Element (sequence i, kv head h, token t, feature c):
+ *   contiguous (page_table == NULL):  i*stride_seq + h*stride_head + t*stride_token + c
+ *   paged:  page = page_table[i*max_pages + t/page_size];
+ *           page*stride_seq + h*stride_head + (t%page_size)*stride_token + c
+ * page_size must be a multiple of block_size, so a block never straddles two pages.
+ * k and v use the same strides.  Tensors larger than 4 GiB are fine (64-bit addressing).
+ */
+typedef struct seer_kv_layout {
+  const void* k;             /* device, bf16 */
+  const void* v;             /* device, bf16 */
+  int64_t stride_seq;        /* elements between sequences (contiguous) or pages (paged) */
+  int64_t stride_head;       /* elements between kv heads   */
+  int64_t stride_token;      /* elements between tokens, >= d */
+  const int32_t* page_table; /* device [B, max_pages] physical page ids, or NULL */
+  int32_t max_pages;
+  int32_t page_size;
+} seer_kv_layout;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int seer_version(void);
+
+/* Static, never-NULL description of a status code. */
+const char* seer_status_string(int status);
+
+/* Bytes of workspace seer_gate_select needs for these sizes (host call, no device work). */
+seer_status seer_gate_workspace_bytes(int B, int Hkv, int nb_max, size_t* bytes /* host, out */);
+
+/*
+ * Bytes of workspace seer_sparse_decode / seer_dense_decode need.  max_blocks is max_sel for
+ * the sparse call and the largest number of blocks of any sequence for the dense call.
+ */
+seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_blocks,
+                                        size_t* bytes /* host, out */);
+
+/*
+ * AttnGate block selection (Eq. 1c; Sec. 3.1; Sec. 3.2).
+ *
+ * For every (sequence i, kv head h), with S = seqlens[i], nfull = S / block_size full blocks,
+ * nb = ceil(S / block_size) blocks (both capped at nb_max):
+ *   score s_j = sum_c q_gate[i,h,c] * kc_cache[i,h,j,c] for j < nfull, accumulated in fp64 (the
+ *   bf16 products are exact, so the score is the exact dot product for all practical inputs);
+ *   entries j >= nfull are never read (a partial block's entry is stale, Sec. 3.2).
+ *   TOPK:      k = budget_blocks ? budget_blocks[i] : ceil(budget_tokens / block_size), clamped
+ *              to [0, min(nb, max_sel)].  If the last block is partial it is selected and uses
+ *              one of the k slots; the remaining slots go to the highest-scoring full blocks,
+ *              equal scores resolved towards the lower block index.  k = 0 selects nothing.
+ *   THRESHOLD: S_j = softmax_j(s_j / sqrt(Dg)) over the full blocks, in fp64; blocks with
+ *              S_j > threshold (strict) are selected, plus the last block if it is partial.
+ * Output: block_idx[i,h,0..n) ascending block ids, block_idx[i,h,n..max_sel) = -1, nblk[i,h] = n.
+ *
+ * q_gate   bf16 [B,Hkv,Dg] contiguous.
+ * kc_cache bf16, element (i,h,j,c) at i*kc_stride_batch + h*kc_stride_head + j*kc_stride_block + c.
+ * seqlens  int32 [B]: tokens in the cache including the current one.
+ * budget_blocks int32 [B] or NULL.  threshold is only read in THRESHOLD mode.
+ * Errors: THRESHOLD mode needs max_sel >= nb_max (SEER_ERR_CAPACITY); TOPK mode with a token
+ * budget needs max_sel >= min(ceil(budget_tokens/block_size), nb_max) (SEER_ERR_CAPACITY).
+ */
+seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t kc_stride_batch,
+                             int64_t kc_stride_head, int64_t kc_stride_block,
+                             const int32_t* seqlens, int B, int Hkv, int Dg, int nb_max,
+                             int block_size, seer_select_mode mode, int32_t budget_tokens,
+                             const int32_t* budget_blocks, double threshold,
+                             int32_t* block_idx /* out [B,Hkv,max_sel] */,
+                             int32_t* nblk /* out [B,Hkv] */, int max_sel, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * Block-sparse flash-decoding (Sec. 3.3).
+ *
+ * For every (sequence i, kv head h) and each of its g = Hq/Hkv query heads (query head hq
+ * belongs to kv head hq / g):  T = tokens of the blocks listed in
+ * block_idx[i,h,0..min(nblk[i,h],max_sel)), a block j covering [j*block_size,
+ * min((j+1)*block_size, seqlens[i]));  x_t = scale * q.K_t;  lse = log sum_T exp(x_t);
+ * out = sum_T exp(x_t - lse) V_t.  Entries < 0 or >= ceil(seqlens[i]/block_size) are skipped;
+ * the list need not be sorted; duplicate entries are a caller error (the block would count
+ * twice).  An empty T gives out = 0 and lse = -inf.  Accumulation is fp32.
+ *
+ * q bf16 [B,Hq,d]; out [B,Hq,d] of out_dtype; lse fp32 [B,Hq] (natural log; may be NULL).
+ */
+seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv /* host struct */,
+                               const int32_t* seqlens, const int32_t* block_idx,
+                               const int32_t* nblk, int max_sel, int B, int Hq, int Hkv, int d,
+                               int block_size, float scale, void* out, seer_dtype out_dtype,
+                               float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Dense flash-decode over all ceil(seqlens[i]/block_size) blocks of every sequence: the
+ * baseline the sparse kernel's speed-up is measured against (Sec. 4.4).  max_blocks >= the
+ * largest block count of any sequence (blocks beyond it are not visited).
+ */
+seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv /* host struct */,
+                              const int32_t* seqlens, int max_blocks, int B, int Hq, int Hkv, int d,
+                              int block_size, float scale, void* out, seer_dtype out_dtype,
+                              float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning knobs (process-wide, host call).  Unknown knobs return SEER_ERR_UNSUPPORTED.
+ *   SEER_KNOB_DECODE_IMPL    0 = auto, 1 = VALU kernel, 2 = MFMA kernel
+ *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
+ */
+typedef enum seer_knob { SEER_KNOB_DECODE_IMPL = 0, SEER_KNOB_DECODE_SPLITS = 1 } seer_knob;
+seer_status seer_set_knob(int knob, int value);
+seer_status seer_get_knob(int knob, int* value /* host, out */);
+
+/*
+ * Per-kernel timing for the bench.  While enabled, each kernel launch of the calls above is
+ * bracketed by HIP events on the caller's stream.  seer_profile_read synchronises on the
+ * recorded events and returns, for the kernel class `which`, the number of launches seen
+ * since the last reset and their total duration in milliseconds.
+ */
+typedef enum seer_kernel_class {
+  SEER_KERNEL_GATE_SCORE = 0,
+  SEER_KERNEL_GATE_SELECT = 1,
+  SEER_KERNEL_DECODE_SPLIT = 2,
+  SEER_KERNEL_DECODE_MERGE = 3,
+  SEER_KERNEL_CLASSES = 4
+} seer_kernel_class;
+seer_status seer_profile_enable(int on);
+seer_status seer_profile_reset(void);
+seer_status seer_profile_read(int which, int* launches /* host, out */, double* total_ms /* host, out */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEER_H */

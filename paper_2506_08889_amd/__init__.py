@@ -1,0 +1,10 @@
+"""MI355X-native decode hot path of SeerAttention-R: AttnGate block selection and
+block-sparse flash-decoding, as hand-written gfx950 HIP kernels behind a small C ABI
+(``include/seer.h``).  This package is only the thin Python binding: argument marshalling,
+no arithmetic.  PyTorch is used for device memory and streams.
+"""
+from .api import (  # noqa: F401
+    SELECT_THRESHOLD, SELECT_TOPK, KERNEL_CLASSES, SeerError, dense_decode, decode_workspace_bytes,
+    gate_select, gate_workspace_bytes, get_knob, lib_path, load_library, profile_enable, profile_read,
+    profile_reset, set_knob, sparse_decode, version,
+)

@@ -1,0 +1,273 @@
+"""ctypes binding of libseer.so.  Same names as the C entry points (minus the ``seer_``
+prefix); every function only checks dtypes/devices, extracts pointers, strides and the
+current HIP stream, and forwards.  There is no CPU fallback: if the library cannot be loaded
+the import of a function's first use raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libseer.so")
+_lib = None
+
+SELECT_TOPK = 0
+SELECT_THRESHOLD = 1
+KNOB_DECODE_IMPL = 0
+KNOB_DECODE_SPLITS = 1
+KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge")
+
+
+class SeerError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn} failed: {text} (status {status})")
+        self.status = status
+
+
+class _KVLayout(ctypes.Structure):
+    _fields_ = [
+        ("k", ctypes.c_void_p),
+        ("v", ctypes.c_void_p),
+        ("stride_seq", ctypes.c_int64),
+        ("stride_head", ctypes.c_int64),
+        ("stride_token", ctypes.c_int64),
+        ("page_table", ctypes.c_void_p),
+        ("max_pages", ctypes.c_int32),
+        ("page_size", ctypes.c_int32),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libseer.so (building it first only if it is not there)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_int, c_i64, c_vp, c_sz = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    lib.seer_version.restype = c_int
+    lib.seer_status_string.restype = ctypes.c_char_p
+    lib.seer_status_string.argtypes = [c_int]
+    lib.seer_gate_workspace_bytes.restype = c_int
+    lib.seer_gate_workspace_bytes.argtypes = [c_int, c_int, c_int, ctypes.POINTER(c_sz)]
+    lib.seer_decode_workspace_bytes.restype = c_int
+    lib.seer_decode_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, ctypes.POINTER(c_sz)]
+    lib.seer_gate_select.restype = c_int
+    lib.seer_gate_select.argtypes = [c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_int, c_int, c_int, c_int,
+                                     c_int, c_int, ctypes.c_int32, c_vp, ctypes.c_double, c_vp, c_vp,
+                                     c_int, c_vp, c_sz, c_vp]
+    lib.seer_sparse_decode.restype = c_int
+    lib.seer_sparse_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int,
+                                       c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
+                                       c_vp, c_sz, c_vp]
+    lib.seer_dense_decode.restype = c_int
+    lib.seer_dense_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int,
+                                      c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.seer_set_knob.restype = c_int
+    lib.seer_set_knob.argtypes = [c_int, c_int]
+    lib.seer_get_knob.restype = c_int
+    lib.seer_get_knob.argtypes = [c_int, ctypes.POINTER(c_int)]
+    lib.seer_profile_enable.restype = c_int
+    lib.seer_profile_enable.argtypes = [c_int]
+    lib.seer_profile_reset.restype = c_int
+    lib.seer_profile_read.restype = c_int
+    lib.seer_profile_read.argtypes = [c_int, ctypes.POINTER(c_int), ctypes.POINTER(ctypes.c_double)]
+    _lib = lib
+    return lib
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise SeerError(fn, status, load_library().seer_status_string(status).decode())
+
+
+def version() -> int:
+    return int(load_library().seer_version())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _want(t: torch.Tensor, dtype, name: str):
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor")
+
+
+def gate_workspace_bytes(B: int, Hkv: int, nb_max: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check("seer_gate_workspace_bytes", load_library().seer_gate_workspace_bytes(B, Hkv, nb_max, ctypes.byref(n)))
+    return int(n.value)
+
+
+def decode_workspace_bytes(B: int, Hq: int, Hkv: int, d: int, max_blocks: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check("seer_decode_workspace_bytes",
+           load_library().seer_decode_workspace_bytes(B, Hq, Hkv, d, max_blocks, ctypes.byref(n)))
+    return int(n.value)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def gate_select(q_gate: torch.Tensor, kc_cache: torch.Tensor, seqlens: torch.Tensor, block_size: int, *,
+                mode: int = SELECT_TOPK, budget_tokens: int = 0, budget_blocks: Optional[torch.Tensor] = None,
+                threshold: float = 0.0, max_sel: int, block_idx: Optional[torch.Tensor] = None,
+                nblk: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """seer_gate_select.  q_gate [B,Hkv,Dg] bf16, kc_cache [B,Hkv,nb_max,Dg] bf16 (last dim
+    contiguous), seqlens [B] int32.  Returns (block_idx [B,Hkv,max_sel] int32, nblk [B,Hkv] int32)."""
+    lib = load_library()
+    _want(q_gate, torch.bfloat16, "q_gate"); _want(kc_cache, torch.bfloat16, "kc_cache")
+    _want(seqlens, torch.int32, "seqlens")
+    B, Hkv, Dg = q_gate.shape
+    if kc_cache.dim() != 4 or kc_cache.shape[0] != B or kc_cache.shape[1] != Hkv or kc_cache.shape[3] != Dg:
+        raise ValueError("kc_cache must be [B,Hkv,nb_max,Dg]")
+    if kc_cache.stride(3) != 1 or not q_gate.is_contiguous() or not seqlens.is_contiguous():
+        raise ValueError("q_gate/seqlens must be contiguous and kc_cache contiguous in its last dim")
+    nb_max = kc_cache.shape[2]
+    dev = q_gate.device
+    if block_idx is None:
+        block_idx = torch.empty(B, Hkv, max_sel, dtype=torch.int32, device=dev)
+    if nblk is None:
+        nblk = torch.empty(B, Hkv, dtype=torch.int32, device=dev)
+    _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk")
+    if budget_blocks is not None:
+        _want(budget_blocks, torch.int32, "budget_blocks")
+    need = gate_workspace_bytes(B, Hkv, nb_max)
+    if workspace is None:
+        workspace = _workspace(need, dev)
+    st = lib.seer_gate_select(_ptr(q_gate), _ptr(kc_cache), kc_cache.stride(0), kc_cache.stride(1),
+                              kc_cache.stride(2), _ptr(seqlens), B, Hkv, Dg, nb_max, block_size, mode,
+                              int(budget_tokens), _ptr(budget_blocks), float(threshold), _ptr(block_idx),
+                              _ptr(nblk), max_sel, _ptr(workspace), workspace.numel(), _stream())
+    _check("seer_gate_select", st)
+    return block_idx, nblk
+
+
+def _layout(k: torch.Tensor, v: torch.Tensor, page_table: Optional[torch.Tensor], page_size: int) -> _KVLayout:
+    _want(k, torch.bfloat16, "k"); _want(v, torch.bfloat16, "v")
+    if k.dim() != 4 or k.shape != v.shape or k.stride() != v.stride() or k.stride(3) != 1:
+        raise ValueError("k and v must be 4-D, same shape and strides, contiguous in the last dim")
+    lay = _KVLayout()
+    lay.k = k.data_ptr()
+    lay.v = v.data_ptr()
+    lay.stride_seq, lay.stride_head, lay.stride_token = k.stride(0), k.stride(1), k.stride(2)
+    if page_table is not None:
+        _want(page_table, torch.int32, "page_table")
+        if not page_table.is_contiguous():
+            raise ValueError("page_table must be contiguous")
+        lay.page_table = page_table.data_ptr()
+        lay.max_pages = page_table.shape[1]
+        lay.page_size = page_size
+    else:
+        lay.page_table = None
+        lay.max_pages = 0
+        lay.page_size = 0
+    return lay
+
+
+def _decode_out(q, out, lse, out_dtype):
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty(B, Hq, d, dtype=out_dtype, device=q.device)
+    if out.dtype not in (torch.bfloat16, torch.float32) or not out.is_contiguous():
+        raise TypeError("out must be contiguous bf16 or fp32")
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    _want(lse, torch.float32, "lse")
+    return out, lse
+
+
+def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor,
+                  block_idx: torch.Tensor, nblk: torch.Tensor, block_size: int, scale: float, *,
+                  page_table: Optional[torch.Tensor] = None, page_size: int = 0,
+                  out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                  out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+    """seer_sparse_decode.  q [B,Hq,d] bf16; k/v contiguous [B,Hkv,S,d] views or paged pools
+    [n_pages,Hkv,page,d] with page_table [B,max_pages]; block_idx [B,Hkv,max_sel], nblk [B,Hkv]
+    int32.  Returns (out [B,Hq,d], lse [B,Hq] fp32)."""
+    lib = load_library()
+    _want(q, torch.bfloat16, "q"); _want(seqlens, torch.int32, "seqlens")
+    _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk")
+    if not (q.is_contiguous() and block_idx.is_contiguous() and nblk.is_contiguous()):
+        raise ValueError("q, block_idx and nblk must be contiguous")
+    B, Hq, d = q.shape
+    Hkv = k.shape[1]
+    max_sel = block_idx.shape[2]
+    lay = _layout(k, v, page_table, page_size)
+    out, lse = _decode_out(q, out, lse, out_dtype)
+    need = decode_workspace_bytes(B, Hq, Hkv, d, max_sel)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    st = lib.seer_sparse_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
+                                max_sel, B, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
+                                0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
+                                workspace.numel(), _stream())
+    _check("seer_sparse_decode", st)
+    return out, lse
+
+
+def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor, max_blocks: int,
+                 block_size: int, scale: float, *, page_table: Optional[torch.Tensor] = None,
+                 page_size: int = 0, out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                 out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+    """seer_dense_decode: the same kernels over every block of every sequence."""
+    lib = load_library()
+    _want(q, torch.bfloat16, "q"); _want(seqlens, torch.int32, "seqlens")
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    B, Hq, d = q.shape
+    Hkv = k.shape[1]
+    lay = _layout(k, v, page_table, page_size)
+    out, lse = _decode_out(q, out, lse, out_dtype)
+    need = decode_workspace_bytes(B, Hq, Hkv, d, max_blocks)
+    if workspace is None:
+        workspace = _workspace(need, q.device)
+    st = lib.seer_dense_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), max_blocks, B, Hq, Hkv, d,
+                               block_size, ctypes.c_float(scale), _ptr(out),
+                               0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
+                               workspace.numel(), _stream())
+    _check("seer_dense_decode", st)
+    return out, lse
+
+
+def set_knob(knob: int, value: int):
+    _check("seer_set_knob", load_library().seer_set_knob(knob, value))
+
+
+def get_knob(knob: int) -> int:
+    v = ctypes.c_int(0)
+    _check("seer_get_knob", load_library().seer_get_knob(knob, ctypes.byref(v)))
+    return int(v.value)
+
+
+def profile_enable(on: bool):
+    _check("seer_profile_enable", load_library().seer_profile_enable(1 if on else 0))
+
+
+def profile_reset():
+    _check("seer_profile_reset", load_library().seer_profile_reset())
+
+
+def profile_read(which: int):
+    """(launches, total_ms) of one kernel class since the last reset."""
+    n = ctypes.c_int(0)
+    ms = ctypes.c_double(0.0)
+    _check("seer_profile_read", load_library().seer_profile_read(which, ctypes.byref(n), ctypes.byref(ms)))
+    return int(n.value), float(ms.value)

@@ -1,0 +1,323 @@
+// Host side of the C ABI declared in include/seer.h: argument validation, split planning,
+// workspace carving and kernel launches.  Nothing here allocates device memory or
+// synchronises the stream (the optional profiling path creates HIP events).
+#include "../../include/seer.h"
+
+#include <math.h>
+
+#include <mutex>
+#include <vector>
+
+#include "seer_internal.h"
+
+namespace {
+
+int g_knob_impl = 0;
+int g_knob_splits = 0;
+
+struct ProfEvent { int cls; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfEvent> g_prof;
+std::mutex g_prof_mu;
+
+int cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+    else
+      cus = 256;   // MI355X
+    (void)hipGetLastError();
+  }
+  return cus;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// How the block list is cut: num_splits slices of blocks_per_split list entries each (the
+// partition runs over the list capacity, not over the blocks of the sequence, Sec. 3.3).
+void plan_splits(int B, int Hkv, int max_blocks, int* num_splits, int* blocks_per_split) {
+  const long groups = (long)B * Hkv;
+  const long want_wgs = (long)cu_count() * 4;
+  long ns = g_knob_splits > 0 ? g_knob_splits : (want_wgs + groups - 1) / groups;
+  const long min_len = 4;   // at least one block per wave of a work-group
+  long max_ns = (max_blocks + min_len - 1) / min_len;
+  if (max_ns < 1) max_ns = 1;
+  if (ns > max_ns) ns = max_ns;
+  if (ns > 256) ns = 256;
+  if (ns < 1) ns = 1;
+  long len = (max_blocks + ns - 1) / ns;
+  if (len < 1) len = 1;
+  ns = (max_blocks + len - 1) / len;
+  if (ns < 1) ns = 1;
+  *num_splits = (int)ns;
+  *blocks_per_split = (int)len;
+}
+
+size_t decode_ws_bytes(int B, int Hkv, int g, int num_splits) {
+  const size_t parts = (size_t)B * Hkv * num_splits * g;
+  return align_up(parts * seer::kHeadDim * sizeof(float), 256) + align_up(parts * 2 * sizeof(float), 256);
+}
+
+struct Timed {
+  int cls;
+  hipStream_t s;
+  hipEvent_t a = nullptr, b = nullptr;
+  bool on;
+  Timed(int c, hipStream_t st) : cls(c), s(st), on(g_prof_on) {
+    if (on) {
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+      (void)hipEventRecord(a, s);
+    }
+  }
+  ~Timed() {
+    if (on) {
+      (void)hipEventRecord(b, s);
+      std::lock_guard<std::mutex> lk(g_prof_mu);
+      g_prof.push_back({cls, a, b});
+    }
+  }
+};
+
+bool block_size_ok(int bs) { return bs == 16 || bs == 32 || bs == 64 || bs == 128; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
+                          const int32_t* block_idx, const int32_t* nblk, int max_blocks, bool sparse,
+                          int B, int Hq, int Hkv, int d, int block_size, float scale, void* out,
+                          seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  if (!q || !kv || !seqlens || !out) return SEER_ERR_NULL;
+  if (!kv->k || !kv->v) return SEER_ERR_NULL;
+  if (sparse && (!block_idx || !nblk)) return SEER_ERR_NULL;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || d <= 0 || block_size <= 0) return SEER_ERR_SHAPE;
+  if (Hq % Hkv != 0) return SEER_ERR_SHAPE;
+  if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
+  const int g = Hq / Hkv;
+  if (d != seer::kHeadDim || g > seer::kMaxGroup || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
+  if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
+    return SEER_ERR_SHAPE;
+  if (!aligned16(kv->k) || !aligned16(kv->v) || !aligned16(q)) return SEER_ERR_SHAPE;
+  if (kv->page_table) {
+    if (kv->page_size <= 0 || kv->max_pages <= 0 || kv->page_size % block_size != 0) return SEER_ERR_SHAPE;
+  }
+  int ns, len;
+  plan_splits(B, Hkv, max_blocks, &ns, &len);
+  const size_t need = decode_ws_bytes(B, Hkv, g, ns);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SEER_ERR_WORKSPACE;
+
+  seer::DecodeParams p{};
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(kv->k);
+  p.v = static_cast<const uint16_t*>(kv->v);
+  p.stride_seq = kv->stride_seq;
+  p.stride_head = kv->stride_head;
+  p.stride_token = kv->stride_token;
+  p.page_table = kv->page_table;
+  p.max_pages = kv->max_pages;
+  p.page_size = kv->page_size;
+  p.seqlens = seqlens;
+  p.block_idx = sparse ? block_idx : nullptr;
+  p.nblk = sparse ? nblk : nullptr;
+  p.max_blocks = max_blocks;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.g = g; p.block_size = block_size;
+  p.scale_log2e = (float)((double)scale * 1.4426950408889634);
+  p.num_splits = ns;
+  p.blocks_per_split = len;
+  const size_t parts = (size_t)B * Hkv * ns * g;
+  p.part_acc = static_cast<float*>(workspace);
+  p.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                       align_up(parts * seer::kHeadDim * sizeof(float), 256));
+  p.out = out;
+  p.lse = lse;
+  p.out_is_f32 = out_dtype == SEER_F32;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  bool use_mfma = (block_size % 32 == 0);
+  if (g_knob_impl == 1) use_mfma = false;
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_DECODE_SPLIT, s);
+    e = use_mfma ? seer::launch_decode_split_mfma(p, s) : seer::launch_decode_split_valu(p, s);
+  }
+  if (e != hipSuccess) return SEER_ERR_HIP;
+  {
+    Timed t(SEER_KERNEL_DECODE_MERGE, s);
+    e = seer::launch_decode_merge(p, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int seer_version(void) { return 100; }
+
+const char* seer_status_string(int status) {
+  switch (status) {
+    case SEER_OK: return "ok";
+    case SEER_ERR_NULL: return "a required pointer is NULL";
+    case SEER_ERR_SHAPE: return "bad or inconsistent sizes, strides or alignment";
+    case SEER_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SEER_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SEER_ERR_CAPACITY: return "max_sel cannot hold the requested selection";
+    case SEER_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+seer_status seer_gate_workspace_bytes(int B, int Hkv, int nb_max, size_t* bytes) {
+  if (!bytes) return SEER_ERR_NULL;
+  if (B <= 0 || Hkv <= 0 || nb_max <= 0) return SEER_ERR_SHAPE;
+  *bytes = align_up((size_t)B * Hkv * nb_max * sizeof(double), 256);
+  return SEER_OK;
+}
+
+seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_blocks, size_t* bytes) {
+  if (!bytes) return SEER_ERR_NULL;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || Hq % Hkv) return SEER_ERR_SHAPE;
+  if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup) return SEER_ERR_UNSUPPORTED;
+  int ns, len;
+  plan_splits(B, Hkv, max_blocks, &ns, &len);
+  *bytes = decode_ws_bytes(B, Hkv, Hq / Hkv, ns);
+  return SEER_OK;
+}
+
+seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t kc_stride_batch,
+                             int64_t kc_stride_head, int64_t kc_stride_block, const int32_t* seqlens,
+                             int B, int Hkv, int Dg, int nb_max, int block_size, seer_select_mode mode,
+                             int32_t budget_tokens, const int32_t* budget_blocks, double threshold,
+                             int32_t* block_idx, int32_t* nblk, int max_sel, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!q_gate || !kc_cache || !seqlens || !block_idx || !nblk) return SEER_ERR_NULL;
+  if (B <= 0 || Hkv <= 0 || Dg <= 0 || nb_max <= 0 || block_size <= 0 || max_sel <= 0) return SEER_ERR_SHAPE;
+  if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
+  if (Dg != seer::kHeadDim || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  if (mode != SEER_SELECT_TOPK && mode != SEER_SELECT_THRESHOLD) return SEER_ERR_UNSUPPORTED;
+  if ((kc_stride_batch % 8) || (kc_stride_head % 8) || (kc_stride_block % 8) || kc_stride_block < Dg)
+    return SEER_ERR_SHAPE;
+  if (!aligned16(q_gate) || !aligned16(kc_cache)) return SEER_ERR_SHAPE;
+  if (mode == SEER_SELECT_THRESHOLD) {
+    if (!(threshold == threshold)) return SEER_ERR_SHAPE;   // NaN
+    if (max_sel < nb_max) return SEER_ERR_CAPACITY;
+  } else if (!budget_blocks) {
+    if (budget_tokens < 0) return SEER_ERR_SHAPE;
+    long k = ((long)budget_tokens + block_size - 1) / block_size;
+    if (k > nb_max) k = nb_max;
+    if (max_sel < k) return SEER_ERR_CAPACITY;
+  }
+  size_t need = 0;
+  seer_gate_workspace_bytes(B, Hkv, nb_max, &need);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SEER_ERR_WORKSPACE;
+
+  seer::GateParams p{};
+  p.q_gate = static_cast<const uint16_t*>(q_gate);
+  p.kc = static_cast<const uint16_t*>(kc_cache);
+  p.kc_stride_batch = kc_stride_batch;
+  p.kc_stride_head = kc_stride_head;
+  p.kc_stride_block = kc_stride_block;
+  p.seqlens = seqlens;
+  p.B = B; p.Hkv = Hkv; p.nb_max = nb_max; p.block_size = block_size;
+  p.mode = (int)mode;
+  p.budget_tokens = budget_tokens;
+  p.budget_blocks = budget_blocks;
+  p.threshold = threshold;
+  p.inv_sqrt_dg = 1.0 / sqrt((double)Dg);
+  p.block_idx = block_idx;
+  p.nblk = nblk;
+  p.max_sel = max_sel;
+  p.scores = static_cast<double*>(workspace);
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_GATE_SCORE, s);
+    e = seer::launch_gate_score(p, s);
+  }
+  if (e != hipSuccess) return SEER_ERR_HIP;
+  {
+    Timed t(SEER_KERNEL_GATE_SELECT, s);
+    e = seer::launch_gate_select(p, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
+seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
+                               const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int Hq,
+                               int Hkv, int d, int block_size, float scale, void* out,
+                               seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, Hq, Hkv, d, block_size, scale,
+                       out, out_dtype, lse, workspace, workspace_bytes, stream);
+}
+
+seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int32_t* seqlens, int max_blocks,
+                              int B, int Hq, int Hkv, int d, int block_size, float scale, void* out,
+                              seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, Hq, Hkv, d, block_size,
+                       scale, out, out_dtype, lse, workspace, workspace_bytes, stream);
+}
+
+seer_status seer_set_knob(int knob, int value) {
+  switch (knob) {
+    case SEER_KNOB_DECODE_IMPL:
+      if (value < 0 || value > 2) return SEER_ERR_SHAPE;
+      g_knob_impl = value;
+      return SEER_OK;
+    case SEER_KNOB_DECODE_SPLITS:
+      if (value < 0) return SEER_ERR_SHAPE;
+      g_knob_splits = value;
+      return SEER_OK;
+    default: return SEER_ERR_UNSUPPORTED;
+  }
+}
+
+seer_status seer_get_knob(int knob, int* value) {
+  if (!value) return SEER_ERR_NULL;
+  switch (knob) {
+    case SEER_KNOB_DECODE_IMPL: *value = g_knob_impl; return SEER_OK;
+    case SEER_KNOB_DECODE_SPLITS: *value = g_knob_splits; return SEER_OK;
+    default: return SEER_ERR_UNSUPPORTED;
+  }
+}
+
+seer_status seer_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return SEER_OK;
+}
+
+seer_status seer_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (auto& e : g_prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  g_prof.clear();
+  return SEER_OK;
+}
+
+seer_status seer_profile_read(int which, int* launches, double* total_ms) {
+  if (!launches || !total_ms) return SEER_ERR_NULL;
+  if (which < 0 || which >= SEER_KERNEL_CLASSES) return SEER_ERR_SHAPE;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int n = 0;
+  double tot = 0.0;
+  for (auto& e : g_prof) {
+    if (e.cls != which) continue;
+    if (hipEventSynchronize(e.b) != hipSuccess) return SEER_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) return SEER_ERR_HIP;
+    tot += ms;
+    ++n;
+  }
+  *launches = n;
+  *total_ms = tot;
+  return SEER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,318 @@
+// Block-sparse flash-decoding, split-K main kernel, MFMA formulation for gfx950 (Sec. 3.3).
+//
+// Grid (num_splits, Hkv, B): a work-group owns one (sequence, kv head) query group and one
+// contiguous slice of its selected-block list (the list is partitioned over its capacity,
+// not over the blocks of the sequence).  Inside the work-group the 4 wavefronts are fully
+// independent: wave w takes the 32-token half-blocks w, w+4, ... of the slice, keeps its own
+// running max / sum / output, and the four are merged once at the end through LDS.  There is
+// no barrier in the main loop.
+//
+// The g query heads of the group are padded to the 16-wide side of v_mfma_f32_16x16x32_bf16.
+// Written for the MFMA operand layout (lane = 16*q + n):
+//   A[i][k]: lane holds row i = n, k = 8q..8q+7      B[k][j]: lane holds column j = n, k = 8q..8q+7
+//   D[i][j]: lane holds column j = n, rows i = 4q..4q+3
+//
+//   S^T = K Q^T   A = 16 tokens x 32 features of K, B = Q^T (head = column).  K rows arrive by
+//                 coalesced 128-bit loads (16 lanes = one 256-byte row), are written to a
+//                 wave-private, XOR-swizzled LDS tile and read back in operand layout.
+//   softmax       D gives each lane 4 tokens of one head (x2 tiles): max over the lane's 8
+//                 values and across q (2 shuffles); exponentials in the base-2 domain.
+//   O^T = V^T P^T B = P^T is exactly the layout D left the probabilities in (tile 0 -> k slots
+//                 0..3, tile 1 -> k slots 4..7 of each lane), so P never moves.  A = V^T needs,
+//                 per lane, 8 tokens of one feature: each lane loads 8 rows x 16 bytes (again
+//                 fully coalesced), and 32 in-lane 16-bit interleaves build the 8 operands;
+//                 operand e covers features {8n+e}.  D then leaves lane (n,q) with
+//                 O[head n][32q .. 32q+31], contiguous.
+//
+// Loads for the next half-block are issued as soon as the registers of the current one have
+// been consumed (K after its copy to LDS, V after the interleave), so each wave keeps 8-16 KiB
+// in flight.
+#include "seer_internal.h"
+
+namespace seer {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+struct HalfBlock {
+  int64_t off;   // element offset of the first token of the half-block
+  int ntok;      // valid tokens (1..32); 0 = no more work
+};
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t x, uint32_t y) { return (x >> 16) | (y & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int i) {
+  return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t r;
+  r[0] = (__bf16)a;
+  r[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+}  // namespace
+
+// ROWS128: stride_token == 128 elements (rows back to back), so every row offset is an immediate.
+template <bool ROWS128>
+__global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodeParams p) {
+  // 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256];
+
+  const int split = blockIdx.x, hk = blockIdx.y, i = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n16 = lane & 15, q4 = lane >> 4;
+  const int g = p.g;
+
+  int S = p.seqlens[i];
+  S = S < 0 ? 0 : S;
+  const int bs = p.block_size;
+  const int nb = (S + bs - 1) / bs;
+  const int64_t grp = (int64_t)i * p.Hkv + hk;
+  const int32_t* list;
+  const int n = group_list(p, grp, nb, &list);
+  const int begin = split * p.blocks_per_split;
+  if (begin >= n) return;
+  const int end = (begin + p.blocks_per_split < n) ? begin + p.blocks_per_split : n;
+  const int hpb = bs >> 5;                 // half-blocks (32 tokens) per block
+  const int nh = (end - begin) * hpb;      // half-blocks in this slice
+  const int64_t st = ROWS128 ? (int64_t)kHeadDim : p.stride_token;
+
+  // ---- Q^T operand: head n16 (zero rows for the padding heads) ---------------------------
+  uint4 qb[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qb[kk] = make_uint4(0, 0, 0, 0);
+    if (n16 < g)
+      qb[kk] = *reinterpret_cast<const uint4*>(
+          p.q + ((int64_t)i * p.Hq + (int64_t)hk * g + n16) * kHeadDim + kk * 32 + q4 * 8);
+  }
+
+  // ---- block descriptors: lane e of a 64-entry chunk holds list entry begin + 64*chunk + e --
+  int loaded_chunk = -1;
+  int64_t d_off = 0;
+  int d_ntok = 0;
+  int hb = wave;
+  auto advance = [&]() -> HalfBlock {
+    HalfBlock r;
+    r.off = 0;
+    r.ntok = 0;
+    while (hb < nh) {
+      const int e = hb / hpb, half = hb - e * hpb;
+      const int chunk = e >> 6;
+      if (chunk != loaded_chunk) {
+        loaded_chunk = chunk;
+        const int pe = begin + chunk * 64 + lane;
+        d_ntok = 0;
+        d_off = 0;
+        if (pe < end) {
+          const int j = list ? list[pe] : pe;
+          bool ok = j >= 0 && j < nb;
+          if (ok && p.page_table) ok = ((int64_t)j * bs) / p.page_size < p.max_pages;
+          if (ok) {
+            d_off = block_offset(p, i, hk, j);
+            d_ntok = (S - j * bs < bs) ? S - j * bs : bs;
+          }
+        }
+      }
+      const int src = e & 63;
+      const int nt_blk = __shfl(d_ntok, src);
+      const int lo = __shfl((int)(uint32_t)(uint64_t)d_off, src);
+      const int hi = __shfl((int)(uint32_t)((uint64_t)d_off >> 32), src);
+      hb += 4;
+      int nt = nt_blk - half * 32;
+      nt = nt > 32 ? 32 : nt;
+      if (nt > 0) {
+        r.off = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo) + (int64_t)half * 32 * st;
+        r.ntok = nt;
+        return r;
+      }
+    }
+    return r;
+  };
+
+  // K rows: load u covers rows 4u + q4 (16 lanes = one row).  V rows: load j covers the token of
+  // k-slot j of this lane's q: tau(q, j) = j < 4 ? 4q + j : 16 + 4q + (j - 4).
+  uint4 kr[8], vr[8];
+  auto load_k = [&](const HalfBlock& b) {
+    const uint16_t* base = p.k + b.off + n16 * 8;
+    if (b.ntok == 32) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) kr[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(4 * u + q4) * st);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        kr[u] = make_uint4(0, 0, 0, 0);
+        if (4 * u + q4 < b.ntok) kr[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(4 * u + q4) * st);
+      }
+    }
+  };
+  auto load_v = [&](const HalfBlock& b) {
+    const uint16_t* base = p.v + b.off + n16 * 8;
+    if (b.ntok == 32) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = (j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4);
+        vr[j] = *reinterpret_cast<const uint4*>(base + (int64_t)row * st);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = (j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4);
+        vr[j] = make_uint4(0, 0, 0, 0);
+        if (row < b.ntok) vr[j] = *reinterpret_cast<const uint4*>(base + (int64_t)row * st);
+      }
+    }
+  };
+
+  unsigned char* kt = smem + wave * (32 * 256);   // this wave's K tile
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4_t oacc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) oacc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  HalfBlock cur = advance();
+  if (cur.ntok > 0) {
+    load_k(cur);
+    load_v(cur);
+  }
+
+  while (cur.ntok > 0) {
+    const HalfBlock nxt = advance();
+
+    // ---- 1. K tile -> LDS (swizzled: 16-byte chunk c of row r lands at chunk c ^ (r & 15)) ---
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int row = 4 * u + q4;
+      *reinterpret_cast<uint4*>(kt + row * 256 + ((n16 ^ (row & 15)) << 4)) = kr[u];
+    }
+    if (nxt.ntok > 0) load_k(nxt);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- 2. S^T = K Q^T for the two 16-token tiles -------------------------------------------
+    f32x4_t sacc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      sacc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      const int row = 16 * t + n16;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const uint4 a = *reinterpret_cast<const uint4*>(kt + row * 256 + (((kk * 4 + q4) ^ n16) << 4));
+        sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                          __builtin_bit_cast(bf16x8_t, qb[kk]), sacc[t], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- 3. online softmax (base-2 domain); lane holds tokens 16t + 4q + r of head n16 -------
+    float x[8];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[t][r] * p.scale_log2e;
+    if (cur.ntok < 32) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (16 * t + 4 * q4 + r >= cur.ntok) x[4 * t + r] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);      // finite: token 0 of the half-block is always valid
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float pr[8], psum = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      pr[c] = __builtin_amdgcn_exp2f(x[c] - m_new);
+      psum += pr[c];
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    if (__ballot(alpha != 1.0f)) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) oacc[e] *= alpha;
+    }
+    uint4 pb;
+    pb.x = pack_bf16(pr[0], pr[1]);
+    pb.y = pack_bf16(pr[2], pr[3]);
+    pb.z = pack_bf16(pr[4], pr[5]);
+    pb.w = pack_bf16(pr[6], pr[7]);
+
+    // ---- 4. O^T += V^T P^T ----------------------------------------------------------------------
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      uint32_t o[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const uint32_t a = dword_of(vr[2 * jj], e >> 1), b = dword_of(vr[2 * jj + 1], e >> 1);
+        o[jj] = (e & 1) ? pack_hi(a, b) : pack_lo(a, b);
+      }
+      const uint4 va = make_uint4(o[0], o[1], o[2], o[3]);
+      oacc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va),
+                                                        __builtin_bit_cast(bf16x8_t, pb), oacc[e], 0, 0, 0);
+    }
+    if (nxt.ntok > 0) load_v(nxt);
+    cur = nxt;
+  }
+
+  // ---- merge the four waves; lane (n16,q4) holds O[head n16][32*q4 + 8*r + e] in oacc[e][r] -------
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  __syncthreads();                                    // K tiles are dead from here on
+  float* sm_acc = reinterpret_cast<float*>(smem);     // [4][8][128]
+  float* sm_ml = sm_acc + 4 * kMaxGroup * kHeadDim;   // [4][8][2]  (16 KiB + 256 B <= 32 KiB)
+  if (n16 < g) {
+    float* dst = sm_acc + ((wave * kMaxGroup + n16) * kHeadDim) + 32 * q4;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[8 * r + e] = oacc[e][r];
+    if (q4 == 0) {
+      sm_ml[(wave * kMaxGroup + n16) * 2 + 0] = m_run;
+      sm_ml[(wave * kMaxGroup + n16) * 2 + 1] = l_run;
+    }
+  }
+  __syncthreads();
+
+  const int64_t pidx = grp * p.num_splits + split;
+  for (int o = tid; o < g * kHeadDim; o += 256) {
+    const int h = o / kHeadDim, dd = o % kHeadDim;
+    float ma = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) ma = fmaxf(ma, sm_ml[(w * kMaxGroup + h) * 2]);
+    float ls = 0.f, a = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = sm_ml[(w * kMaxGroup + h) * 2];
+      const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - ma);
+      ls += sm_ml[(w * kMaxGroup + h) * 2 + 1] * f;
+      a += sm_acc[(w * kMaxGroup + h) * kHeadDim + dd] * f;
+    }
+    p.part_acc[(pidx * g + h) * kHeadDim + dd] = a;
+    if (dd == 0) {
+      p.part_ml[(pidx * g + h) * 2 + 0] = ma;
+      p.part_ml[(pidx * g + h) * 2 + 1] = ls;
+    }
+  }
+}
+
+hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s) {
+  dim3 grid(p.num_splits, p.Hkv, p.B);
+  if (p.stride_token == kHeadDim)
+    hipLaunchKernelGGL(seer_decode_split_mfma_kernel<true>, grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL(seer_decode_split_mfma_kernel<false>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace seer

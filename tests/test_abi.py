@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and reports argument errors before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_08889_amd as seer
+from paper_2506_08889_amd.api import _KVLayout
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "seer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(seer_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = seer.load_library()
+    names = declared_symbols()
+    assert {"seer_gate_select", "seer_sparse_decode", "seer_dense_decode", "seer_gate_workspace_bytes",
+            "seer_decode_workspace_bytes", "seer_status_string", "seer_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"libseer.so does not export {n}"
+    assert seer.version() >= 100
+
+
+def test_status_strings():
+    lib = seer.load_library()
+    seen = set()
+    for code in range(0, -7, -1):
+        s = lib.seer_status_string(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert lib.seer_status_string(-99).decode() == "unknown status"
+
+
+def test_workspace_queries():
+    assert seer.gate_workspace_bytes(64, 8, 2048) >= 64 * 8 * 2048 * 8
+    n = seer.decode_workspace_bytes(64, 40, 8, 128, 205)
+    assert n > 0 and n % 256 == 0
+    with pytest.raises(seer.SeerError) as e:
+        seer.decode_workspace_bytes(1, 7, 2, 128, 16)       # Hq not a multiple of Hkv
+    assert e.value.status == -2
+    with pytest.raises(seer.SeerError) as e:
+        seer.decode_workspace_bytes(1, 8, 2, 64, 16)        # head dim 64 is not built
+    assert e.value.status == -3
+    with pytest.raises(seer.SeerError) as e:
+        seer.decode_workspace_bytes(1, 18, 2, 128, 16)      # group of 9 heads
+    assert e.value.status == -3
+    with pytest.raises(seer.SeerError):
+        seer.gate_workspace_bytes(0, 8, 16)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    """Fake, never-dereferenced device addresses: every call below must fail in validation."""
+    lib = seer.load_library()
+    P = ctypes.c_void_p(0x10000)
+    lay = _KVLayout()
+    lay.k, lay.v = 0x10000, 0x20000
+    lay.stride_seq, lay.stride_head, lay.stride_token = 8 * 1024 * 128, 1024 * 128, 128
+    lay.page_table, lay.max_pages, lay.page_size = None, 0, 0
+    f = ctypes.c_float(0.1)
+
+    def sparse(q=P, layp=ctypes.byref(lay), sl=P, bi=P, nk=P, max_sel=16, B=1, Hq=8, Hkv=2, d=128, bs=64,
+               out=P, dt=0, lse=P, ws=P, wsb=1 << 30):
+        return lib.seer_sparse_decode(q, layp, sl, bi, nk, max_sel, B, Hq, Hkv, d, bs, f, out, dt, lse, ws, wsb, None)
+
+    assert sparse(q=None) == -1
+    assert sparse(bi=None) == -1
+    assert sparse(out=None) == -1
+    assert sparse(layp=None) == -1
+    assert sparse(Hq=7) == -2
+    assert sparse(B=0) == -2
+    assert sparse(d=64) == -3
+    assert sparse(bs=48) == -3
+    assert sparse(Hq=18) == -3
+    assert sparse(dt=5) == -3
+    assert sparse(ws=None) == -4
+    assert sparse(wsb=16) == -4
+    assert sparse(ws=ctypes.c_void_p(0x10008)) == -4            # misaligned workspace
+    assert sparse(q=ctypes.c_void_p(0x10004)) == -2              # misaligned q
+    lay.stride_token = 100
+    assert sparse() == -2
+    lay.stride_token = 128
+    lay.page_table, lay.max_pages, lay.page_size = 0x30000, 4, 96   # page not a multiple of the block
+    assert sparse() == -2
+    lay.page_table, lay.max_pages, lay.page_size = None, 0, 0
+
+    assert lib.seer_dense_decode(P, ctypes.byref(lay), P, 0, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, None) == -2
+    assert lib.seer_dense_decode(None, ctypes.byref(lay), P, 4, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, None) == -1
+
+    def gate(qg=P, kc=P, sl=P, B=1, Hkv=2, Dg=128, nb_max=64, bs=64, mode=0, budget=1024, bb=None, thr=0.0,
+             bi=P, nk=P, max_sel=16, ws=P, wsb=1 << 30, sj=128):
+        return lib.seer_gate_select(qg, kc, 2 * 64 * 128, 64 * 128, sj, sl, B, Hkv, Dg, nb_max, bs, mode, budget,
+                                    bb, thr, bi, nk, max_sel, ws, wsb, None)
+
+    assert gate(qg=None) == -1
+    assert gate(nk=None) == -1
+    assert gate(Dg=64) == -3
+    assert gate(mode=2) == -3
+    assert gate(bs=100) == -3
+    assert gate(budget=-5) == -2
+    assert gate(sj=64) == -2
+    assert gate(max_sel=8) == -5                       # 1024 tokens = 16 blocks do not fit 8 slots
+    assert gate(mode=1, max_sel=16) == -5              # threshold mode may select every block
+    assert gate(mode=1, max_sel=64, thr=float("nan")) == -2
+    assert gate(ws=None) == -4
+    assert gate(wsb=8) == -4
+
+
+def test_knobs_roundtrip():
+    for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0))):
+        for v in vals:
+            seer.set_knob(knob, v)
+            assert seer.get_knob(knob) == v
+    with pytest.raises(seer.SeerError):
+        seer.set_knob(0, 9)
+    with pytest.raises(seer.SeerError):
+        seer.set_knob(42, 1)

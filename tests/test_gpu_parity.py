@@ -1,0 +1,327 @@
+"""GPU parity: the HIP library (through the C ABI) against the fp64 CPU oracle, element by
+element, on seeded synthetic inputs.  Block indices must match bit-exactly; outputs within the
+tolerances in tests/helpers.py.  Sizes are small enough for the oracle to finish in seconds but
+span several tiles, several splits and ragged tails.  (The paper prints no worked numeric
+example; expectations come from the oracle, which tests/test_oracle_pins.py pins.)"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_08889_amd as seer
+import synth
+from helpers import check_decode, check_indices, cpu, oracle_decode, oracle_gate, pick_threshold
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+IMPLS = {"valu": 1, "mfma": 2}
+
+
+@pytest.fixture(autouse=True)
+def _reset_knobs():
+    seer.set_knob(0, 0)
+    seer.set_knob(1, 0)
+    yield
+    seer.set_knob(0, 0)
+    seer.set_knob(1, 0)
+
+
+def gpu_gate(inp, mode=seer.SELECT_TOPK, threshold=0.0, max_sel=None):
+    w = inp.w
+    return seer.gate_select(inp.q_gate, inp.kc, inp.seqlens, w.block_size, mode=mode,
+                            budget_tokens=w.budget_tokens, budget_blocks=inp.budget_blocks,
+                            threshold=threshold, max_sel=max_sel or inp.max_sel)
+
+
+def gpu_decode(inp, block_idx, nblk, out_dtype):
+    w = inp.w
+    return seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, block_idx, nblk, w.block_size, w.scale,
+                              page_table=inp.page_table, page_size=inp.page_size, out_dtype=out_dtype)
+
+
+def run_gate_and_decode(w, impls=("valu", "mfma"), splits=(0,)):
+    print(f"[case] {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} seed={w.seed}", flush=True)
+    inp = synth.make_inputs(w, DEV)
+    ref_idx, ref_cnt = oracle_gate(inp)
+    idx, cnt = gpu_gate(inp)
+    torch.cuda.synchronize()
+    check_indices(idx, cnt, ref_idx, ref_cnt, what=f"{w.name} gate")
+    ref_out, ref_lse = oracle_decode(inp, ref_idx, ref_cnt)
+    for impl in impls:
+        if impl == "mfma" and w.block_size % 32:
+            continue
+        seer.set_knob(0, IMPLS[impl])
+        for ns in splits:
+            seer.set_knob(1, ns)
+            for dt, tight in ((torch.float32, True), (torch.bfloat16, False)):
+                print(f"[decode] {w.name} impl={impl} splits={ns} out={dt}", flush=True)
+                out, lse = gpu_decode(inp, idx, cnt, dt)
+                torch.cuda.synchronize()
+                check_decode(out, lse, ref_out, ref_lse, tight=tight, what=f"{w.name} {impl} ns={ns} {dt}")
+    return inp, idx, cnt, ref_out, ref_lse
+
+
+# ------------------------------------------------------------ the benchmark configurations, scaled
+
+
+def test_c1_tiny_single_layer_full_size():
+    run_gate_and_decode(synth.CONFIGS["c1"], splits=(0, 1, 3))
+
+
+def test_c2_shape_scaled():
+    w = synth.scaled(synth.CONFIGS["c2"], B=3, seqlen=4096 + 64 * 5, budget_tokens=1024)
+    run_gate_and_decode(w, splits=(0, 2))
+
+
+def test_c3_shape_scaled_paged_varlen_outliers():
+    w = synth.scaled(synth.CONFIGS["c3"], B=5, seqlen_range=(900, 6000))
+    inp, idx, cnt, _, _ = run_gate_and_decode(w, splits=(0, 5))
+    # the ragged tail really is exercised
+    assert (inp.seqlens_cpu % w.block_size != 0).any()
+    nb = (inp.seqlens_cpu + w.block_size - 1) // w.block_size
+    last = cpu(idx).gather(2, (cpu(cnt).long() - 1).clamp(min=0).unsqueeze(-1)).squeeze(-1)
+    part = (inp.seqlens_cpu % w.block_size != 0)
+    assert (last[part] == (nb[part] - 1).unsqueeze(-1)).all()
+
+
+def test_c4_shape_scaled_group_of_five():
+    w = synth.scaled(synth.CONFIGS["c4"], B=2, seqlen=8192, budget_tokens=819)
+    run_gate_and_decode(w, splits=(0, 4))
+
+
+@pytest.mark.parametrize("bs", [64, 128])
+def test_c5_shape_scaled_topk_and_threshold(bs):
+    w = synth.scaled(synth.CONFIGS["c5"], B=6, block_size=bs, seqlen_range=(300, 9000), name=f"c5_b{bs}")
+    inp, idx, cnt, _, _ = run_gate_and_decode(w, impls=("mfma",))
+    # threshold mode at several sparsity levels, thresholds placed between adjacent probabilities
+    _, _, scores = oracle_gate(inp, return_scores=True)
+    for keep in (0.5, 0.25, 0.10, 0.05):
+        tau = pick_threshold(scores, inp.seqlens_cpu, bs, w.Dg, keep)
+        ref_idx, ref_cnt = oracle_gate(inp, mode=oracle.SELECT_THRESHOLD, threshold=tau, max_sel=inp.nb_max)
+        print(f"[threshold] {w.name} keep={keep} tau={tau:.6g} selected={int(ref_cnt.sum())}", flush=True)
+        gi, gc = gpu_gate(inp, mode=seer.SELECT_THRESHOLD, threshold=tau, max_sel=inp.nb_max)
+        torch.cuda.synchronize()
+        check_indices(gi, gc, ref_idx, ref_cnt, what=f"{w.name} threshold keep={keep}")
+        ref_out, ref_lse = oracle_decode(inp, ref_idx, ref_cnt)
+        out, lse = gpu_decode(inp, gi, gc, torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"{w.name} threshold keep={keep}")
+
+
+# ------------------------------------------------------------------------------- decode edge cases
+
+
+def small_inputs(seed, B=2, Hq=8, Hkv=2, S=(300, 200), bs=64, paged=False):
+    w = synth.Workload("edge", B=B, Hq=Hq, Hkv=Hkv, block_size=bs, seqlen=max(S), paged=paged,
+                       budget_tokens=bs * 4, seed=seed)       # cache sized for the longest sequence
+    inp = synth.make_inputs(w, "cpu")
+    inp.seqlens_cpu = torch.tensor(S, dtype=torch.int32)
+    inp.seqlens = inp.seqlens_cpu.clone()
+    return inp
+
+
+def to_dev(inp):
+    for f in ("seqlens", "q", "k", "v", "page_table", "q_gate", "kc", "budget_blocks"):
+        t = getattr(inp, f)
+        if t is not None:
+            setattr(inp, f, t.to(DEV))
+    return inp
+
+
+@pytest.mark.parametrize("impl", ["valu", "mfma"])
+def test_invalid_entries_permutation_empty_groups(impl):
+    seer.set_knob(0, IMPLS[impl])
+    inp = to_dev(small_inputs(21, B=3, S=(640, 333, 0)))
+    idx = torch.full((3, 2, 8), -1, dtype=torch.int32)
+    cnt = torch.zeros(3, 2, dtype=torch.int32)
+    idx[0, 0, :6] = torch.tensor([9, 0, -1, 5, 10, 2]); cnt[0, 0] = 6      # unsorted, -1 and 10 (= nb) skipped
+    idx[0, 1, :3] = torch.tensor([99, -7, 3]); cnt[0, 1] = 3
+    idx[1, 0, :4] = torch.tensor([5, 0, 4, 1]); cnt[1, 0] = 4              # block 5 has 13 tokens
+    cnt[1, 1] = 0                                                          # empty selection
+    idx[2, :, 0] = 0; cnt[2, :] = 1                                        # empty sequence
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    for ns in (0, 1, 2, 8):
+        seer.set_knob(1, ns)
+        out, lse = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"edge {impl} ns={ns}")
+    # nblk larger than the list capacity is clamped; negative counts mean empty
+    cnt2 = cnt.clone(); cnt2[0, 0] = 1000; cnt2[0, 1] = -3
+    idx2 = idx.clone()
+    ref_out, ref_lse = oracle_decode(inp, idx2, cnt2)
+    out, lse = gpu_decode(inp, idx2.to(DEV), cnt2.to(DEV), torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"edge {impl} clamped counts")
+
+
+@pytest.mark.parametrize("impl", ["valu", "mfma"])
+@pytest.mark.parametrize("g", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_group_size(impl, g):
+    seer.set_knob(0, IMPLS[impl])
+    inp = to_dev(small_inputs(30 + g, B=2, Hq=2 * g, Hkv=2, S=(777, 130)))
+    gen = torch.Generator().manual_seed(g)
+    nb = (inp.seqlens_cpu + 63) // 64
+    idx, cnt = synth.random_block_lists(2, 2, nb, [7, 2], 7, gen, ascending=False)
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    out, lse = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"g={g} {impl}")
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64, 128])
+def test_block_sizes_and_dense_decode(bs):
+    inp = to_dev(small_inputs(40 + bs, B=2, Hq=8, Hkv=2, S=(1000, 517), bs=bs))
+    nbs = (inp.seqlens_cpu + bs - 1) // bs
+    gen = torch.Generator().manual_seed(bs)
+    k_sel = [max(1, int(n) // 3) for n in nbs]
+    idx, cnt = synth.random_block_lists(2, 2, nbs, k_sel, max(k_sel), gen)
+    # make sure the partial last block of sequence 0 is in one list
+    idx[0, 0, int(cnt[0, 0]) - 1] = int(nbs[0]) - 1
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    out, lse = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"bs={bs} sparse")
+    # dense decode == oracle over all blocks
+    dref_out, dref_lse = oracle_decode(inp, None, None)
+    for impl in ("valu", "mfma"):
+        if impl == "mfma" and bs % 32:
+            continue
+        seer.set_knob(0, IMPLS[impl])
+        w = inp.w
+        out, lse = seer.dense_decode(inp.q, inp.k, inp.v, inp.seqlens, int(nbs.max()), bs, w.scale,
+                                     out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, dref_out, dref_lse, tight=True, what=f"bs={bs} dense {impl}")
+
+
+@pytest.mark.parametrize("impl", ["valu", "mfma"])
+def test_strided_cache_and_page_size_multiple_of_block(impl):
+    seer.set_knob(0, IMPLS[impl])
+    inp = to_dev(small_inputs(50, B=2, S=(512, 448)))
+    B, Hkv, S_alloc, d = inp.k.shape
+    wide_k = torch.zeros(B, Hkv, S_alloc, 2 * d, dtype=torch.bfloat16, device=DEV)
+    wide_v = torch.zeros_like(wide_k)
+    wide_k[..., :d] = inp.k; wide_v[..., :d] = inp.v
+    gen = torch.Generator().manual_seed(5)
+    idx, cnt = synth.random_block_lists(2, 2, [8, 7], [5, 4], 5, gen)
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    w = inp.w
+    out, lse = seer.sparse_decode(inp.q, wide_k[..., :d], wide_v[..., :d], inp.seqlens, idx.to(DEV), cnt.to(DEV),
+                                  64, w.scale, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"strided {impl}")
+    # paged pool whose pages hold two blocks each, pages in reverse order
+    npg = S_alloc // 128
+    pool_k = torch.zeros(B * npg + 1, Hkv, 128, d, dtype=torch.bfloat16, device=DEV)
+    pool_v = torch.zeros_like(pool_k)
+    pt = torch.zeros(B, npg, dtype=torch.int32)
+    for i in range(B):
+        for pg in range(npg):
+            phys = B * npg - (i * npg + pg)
+            pt[i, pg] = phys
+            pool_k[phys] = inp.k[i, :, pg * 128:(pg + 1) * 128]
+            pool_v[phys] = inp.v[i, :, pg * 128:(pg + 1) * 128]
+    out, lse = seer.sparse_decode(inp.q, pool_k, pool_v, inp.seqlens, idx.to(DEV), cnt.to(DEV), 64, w.scale,
+                                  page_table=pt.to(DEV), page_size=128, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"paged x2 {impl}")
+
+
+@pytest.mark.parametrize("impl", ["valu", "mfma"])
+def test_needle_and_large_logits(impl):
+    """One key aligned with a query gives a logit far above the rest (softmax saturates) and
+    a key just past the end of the sequence must never be read."""
+    seer.set_knob(0, IMPLS[impl])
+    inp = small_inputs(60, B=1, Hq=4, Hkv=1, S=(300,))
+    inp.k[0, 0, 299] = (inp.q[0, 1].float() * 6.0).to(torch.bfloat16)      # last valid token of the partial block
+    inp.k[0, 0, 300] = (inp.q[0, 1].float() * 60.0).to(torch.bfloat16)     # beyond the sequence
+    inp.v[0, 0, 300] = 1000.0
+    inp = to_dev(inp)
+    idx = torch.tensor([[[1, 4, 3]]], dtype=torch.int32); cnt = torch.tensor([[3]], dtype=torch.int32)
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    out, lse = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+    torch.cuda.synchronize()
+    check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"needle {impl}")
+    assert abs(float(out[0, 1].float().cpu().numpy() @ np.ones(128)) - float(ref_out[0, 1].sum())) < 0.05
+
+
+def test_long_list_many_chunks_of_descriptors():
+    """A slice longer than 64 list entries (descriptor chunks reload) with one split."""
+    seer.set_knob(1, 1)
+    inp = to_dev(small_inputs(70, B=1, Hq=8, Hkv=2, S=(64 * 200 + 17,)))
+    gen = torch.Generator().manual_seed(70)
+    idx, cnt = synth.random_block_lists(1, 2, [201], [150], 150, gen, ascending=False)
+    idx[0, 0, 70] = 200          # the partial block somewhere in the middle
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    for impl in ("valu", "mfma"):
+        seer.set_knob(0, IMPLS[impl])
+        out, lse = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"long list {impl}")
+
+
+# --------------------------------------------------------------------------------- gate edge cases
+
+
+def test_gate_ties_and_edge_rules_bit_exact():
+    gen = torch.Generator().manual_seed(80)
+    B, Hkv, nb_max, bs = 6, 3, 300, 64
+    qg = torch.randint(-2, 3, (B, Hkv, 128), generator=gen).to(torch.bfloat16)      # many exact ties
+    kc = torch.randint(-1, 2, (B, Hkv, nb_max, 128), generator=gen).to(torch.bfloat16)
+    kc[1] = kc[1, 0, 0]                                                             # all scores equal
+    sl = torch.tensor([300 * bs, 257 * bs, 256 * bs + 1, 5, 0, 64], dtype=torch.int32)
+    for budget in (1, bs, 3 * bs + 1, 100 * bs, 299 * bs, 10 ** 6):
+        max_sel = min((budget + bs - 1) // bs, nb_max)
+        ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_tokens=budget, max_sel=max_sel)
+        gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_tokens=budget, max_sel=max_sel)
+        torch.cuda.synchronize()
+        check_indices(gi, gc, ri, rc, what=f"ties budget={budget}")
+    # per-sequence block budgets, including 0 and more than there are blocks; wider list than needed
+    bb = torch.tensor([7, 0, 400, 3, 2, 1], dtype=torch.int32)
+    ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_blocks=bb, max_sel=310)
+    gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=310)
+    torch.cuda.synchronize()
+    check_indices(gi, gc, ri, rc, what="budget_blocks")
+    # list narrower than a per-sequence budget: clamped to max_sel
+    ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_blocks=bb, max_sel=5)
+    gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=5)
+    torch.cuda.synchronize()
+    check_indices(gi, gc, ri, rc, what="budget_blocks clamped")
+    # threshold: strict comparison on exactly representable probabilities (4 equal scores -> 1/4)
+    kc4 = kc[:, :, :4].clone(); kc4[:] = kc[0, 0, 0]
+    sl4 = torch.full((B,), 4 * bs, dtype=torch.int32)
+    for tau in (0.25, 0.2499999, 0.0, 1.0):
+        ri, rc = oracle.gate_select(qg, kc4, sl4, bs, mode=oracle.SELECT_THRESHOLD, threshold=tau, max_sel=4)
+        gi, gc = seer.gate_select(qg.to(DEV), kc4.to(DEV), sl4.to(DEV), bs, mode=seer.SELECT_THRESHOLD,
+                                  threshold=tau, max_sel=4)
+        torch.cuda.synchronize()
+        check_indices(gi, gc, ri, rc, what=f"threshold tau={tau}")
+
+
+def test_gate_strided_compression_cache_and_long_context():
+    gen = torch.Generator().manual_seed(81)
+    B, Hkv, nb_max, bs = 2, 8, 2048, 64
+    qg = torch.randn(B, Hkv, 128, generator=gen).to(torch.bfloat16)
+    wide = torch.randn(B, Hkv, nb_max, 256, generator=gen).to(torch.bfloat16)
+    kc = wide[..., 128:]                                         # row stride 256, offset 128
+    sl = torch.tensor([131072, 131072 - 63], dtype=torch.int32)
+    ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_tokens=13107, max_sel=205)
+    wd = wide.to(DEV)
+    gi, gc = seer.gate_select(qg.to(DEV), wd[..., 128:], sl.to(DEV), bs, budget_tokens=13107, max_sel=205)
+    torch.cuda.synchronize()
+    check_indices(gi, gc, ri, rc, what="strided kc, 2048 blocks")
+
+
+def test_results_are_deterministic_run_to_run():
+    w = synth.scaled(synth.CONFIGS["c2"], B=2, seqlen=2048, budget_tokens=512)
+    inp = synth.make_inputs(w, DEV)
+    idx, cnt = gpu_gate(inp)
+    a = gpu_decode(inp, idx, cnt, torch.float32)
+    b = gpu_decode(inp, idx, cnt, torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    idx2, cnt2 = gpu_gate(inp)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(cnt, cnt2)
