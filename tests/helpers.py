@@ -23,7 +23,9 @@ LSE_TOL_TIGHT = 2e-4
 
 
 def cpu(t):
-    return None if t is None else t.detach().cpu()
+    if t is None or isinstance(t, np.ndarray):
+        return t
+    return t.detach().cpu()
 
 
 def oracle_decode(inp, block_idx, nblk, group_filter=None):
