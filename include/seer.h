@@ -28,7 +28,8 @@
  *     is launched.  Data-dependent conditions on the device are defined behaviour, not
  *     errors (see each call).
  *   - Supported sizes: head dim d = 128, gate dim Dg = 128, block_size in {16, 32, 64, 128}
- *     ... of which 64 and 128 are the tuned ones, group size Hq/Hkv in 1..8.
+ *     (64 and 128 are the tuned ones; 16 runs on the vector-ALU kernel), group size Hq/Hkv
+ *     in 1..8, at most 65535 sequences and kv heads.
  */
 #ifndef SEER_H
 #define SEER_H
@@ -154,6 +155,14 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv /* host st
                               float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid, not part of the method: a plain streaming read of `bytes` bytes (multiple of
+ * 16) from device memory `src`, no gather and no arithmetic.  Its rate is the practical HBM read
+ * ceiling the decode kernels are compared with.  `sink` is 16 bytes of device memory that the
+ * kernel may write (it practically never does).
+ */
+seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
+/*
  * Tuning knobs (process-wide, host call).  Unknown knobs return SEER_ERR_UNSUPPORTED.
  *   SEER_KNOB_DECODE_IMPL    0 = auto, 1 = VALU kernel, 2 = MFMA kernel
  *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
@@ -173,7 +182,8 @@ typedef enum seer_kernel_class {
   SEER_KERNEL_GATE_SELECT = 1,
   SEER_KERNEL_DECODE_SPLIT = 2,
   SEER_KERNEL_DECODE_MERGE = 3,
-  SEER_KERNEL_CLASSES = 4
+  SEER_KERNEL_STREAM_READ = 4,
+  SEER_KERNEL_CLASSES = 5
 } seer_kernel_class;
 seer_status seer_profile_enable(int on);
 seer_status seer_profile_reset(void);

@@ -18,7 +18,7 @@ SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
-KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge")
+KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read")
 
 
 class SeerError(RuntimeError):
@@ -72,6 +72,8 @@ def load_library():
     lib.seer_dense_decode.restype = c_int
     lib.seer_dense_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int,
                                       c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.seer_hbm_read_probe.restype = c_int
+    lib.seer_hbm_read_probe.argtypes = [c_vp, c_sz, c_vp, c_vp]
     lib.seer_set_knob.restype = c_int
     lib.seer_set_knob.argtypes = [c_int, c_int]
     lib.seer_get_knob.restype = c_int
@@ -245,6 +247,15 @@ def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: tor
                                workspace.numel(), _stream())
     _check("seer_dense_decode", st)
     return out, lse
+
+
+def hbm_read_probe(src: torch.Tensor, sink: torch.Tensor):
+    """seer_hbm_read_probe: stream-read all bytes of `src` (contiguous device tensor)."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.numel() * sink.element_size() >= 16):
+        raise ValueError("src must be a contiguous device tensor and sink hold 16 bytes")
+    nbytes = src.numel() * src.element_size() // 16 * 16
+    _check("seer_hbm_read_probe", load_library().seer_hbm_read_probe(_ptr(src), nbytes, _ptr(sink), _stream()))
+    return nbytes
 
 
 def set_knob(knob: int, value: int):

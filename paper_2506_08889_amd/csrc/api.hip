@@ -39,10 +39,15 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // How the block list is cut: num_splits slices of blocks_per_split list entries each (the
 // partition runs over the list capacity, not over the blocks of the sequence, Sec. 3.3).
+// The split kernels keep 2 work-groups per CU resident; the plan aims at one resident round of
+// work-groups (measured best on MI355X) with at least 4 list entries per slice.
 void plan_splits(int B, int Hkv, int max_blocks, int* num_splits, int* blocks_per_split) {
   const long groups = (long)B * Hkv;
-  const long want_wgs = (long)cu_count() * 4;
-  long ns = g_knob_splits > 0 ? g_knob_splits : (want_wgs + groups - 1) / groups;
+  const long slots = (long)cu_count() * 2;
+  long ns;
+  if (g_knob_splits > 0) ns = g_knob_splits;
+  else if (groups >= slots) ns = 1;
+  else ns = (slots + groups / 2) / groups;
   const long min_len = 4;   // at least one block per wave of a work-group
   long max_ns = (max_blocks + min_len - 1) / min_len;
   if (max_ns < 1) max_ns = 1;
@@ -146,7 +151,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
     e = use_mfma ? seer::launch_decode_split_mfma(p, s) : seer::launch_decode_split_valu(p, s);
   }
   if (e != hipSuccess) return SEER_ERR_HIP;
-  {
+  if (ns > 1) {   // a single slice wrote out and lse itself
     Timed t(SEER_KERNEL_DECODE_MERGE, s);
     e = seer::launch_decode_merge(p, s);
   }
@@ -264,6 +269,18 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int
                               void* stream) {
   return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, Hq, Hkv, d, block_size,
                        scale, out, out_dtype, lse, workspace, workspace_bytes, stream);
+}
+
+seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return SEER_ERR_NULL;
+  if (bytes < 16 || !aligned16(src) || !aligned16(sink)) return SEER_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_STREAM_READ, s);
+    e = seer::launch_stream_read(src, bytes, sink, cu_count() * 8, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
 }
 
 seer_status seer_set_knob(int knob, int value) {

@@ -77,7 +77,10 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   const int32_t* list;
   const int n = group_list(p, grp, nb, &list);
   const int begin = split * p.blocks_per_split;
-  if (begin >= n) return;
+  if (begin >= n) {
+    emit_empty_if_single_split(p, i, hk);
+    return;
+  }
   const int end = (begin + p.blocks_per_split < n) ? begin + p.blocks_per_split : n;
   const int hpb = bs >> 5;                 // half-blocks (32 tokens) per block
   const int nh = (end - begin) * hpb;      // half-blocks in this slice
@@ -284,7 +287,6 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   }
   __syncthreads();
 
-  const int64_t pidx = grp * p.num_splits + split;
   for (int o = tid; o < g * kHeadDim; o += 256) {
     const int h = o / kHeadDim, dd = o % kHeadDim;
     float ma = -INFINITY;
@@ -298,11 +300,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
       ls += sm_ml[(w * kMaxGroup + h) * 2 + 1] * f;
       a += sm_acc[(w * kMaxGroup + h) * kHeadDim + dd] * f;
     }
-    p.part_acc[(pidx * g + h) * kHeadDim + dd] = a;
-    if (dd == 0) {
-      p.part_ml[(pidx * g + h) * 2 + 0] = ma;
-      p.part_ml[(pidx * g + h) * 2 + 1] = ls;
-    }
+    emit_slice(p, i, hk, split, h, dd, ma, ls, a);
   }
 }
 

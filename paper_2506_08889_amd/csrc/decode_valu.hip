@@ -31,7 +31,10 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
   const int32_t* list;
   const int n = group_list(p, grp, nb, &list);
   const int begin = split * p.blocks_per_split;
-  if (begin >= n) return;
+  if (begin >= n) {
+    emit_empty_if_single_split(p, i, hk);
+    return;
+  }
   const int end = (begin + p.blocks_per_split < n) ? begin + p.blocks_per_split : n;
 
   float qf[G][8];
@@ -129,7 +132,6 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
   __syncthreads();
 
   // ---- merge the 4 waves and write the partial of this split --------------------------------
-  const int64_t pidx = grp * p.num_splits + split;
   for (int o = tid; o < G * kHeadDim; o += 256) {
     const int h = o / kHeadDim, dd = o % kHeadDim;
     float ma = -INFINITY;
@@ -143,11 +145,7 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
       ls += sm_ml[w][h][1] * f;
       a += sm_acc[w][h][dd] * f;
     }
-    p.part_acc[(pidx * G + h) * kHeadDim + dd] = a;
-    if (dd == 0) {
-      p.part_ml[(pidx * G + h) * 2 + 0] = ma;
-      p.part_ml[(pidx * G + h) * 2 + 1] = ls;
-    }
+    emit_slice(p, i, hk, split, h, dd, ma, ls, a);
   }
 }
 

@@ -70,15 +70,21 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Select kernel: one work-group per (sequence, kv head).
-//   top-k:     radix select (8 passes of 8 bits over order-preserving 64-bit keys) finds the
-//              k-th largest score and how many blocks equal to it are still needed; an
-//              ordered compaction then emits, in ascending block order, every block above
-//              it plus the first `need` blocks equal to it (lowest index wins a tie).
-//   threshold: fp64 softmax over the full blocks (max, sum of exp, divide) and the same
-//              ordered compaction on S_j > tau.
-// The scores of one group are at most a few thousand doubles and stay in L2 across passes.
+// Select kernel: one work-group per (sequence, kv head).  The scores of the group are first
+// copied into LDS (up to kSelectLdsBlocks of them; longer caches are re-read from L2).
+//   top-k:     radix select over order-preserving 64-bit keys, 8 bits per pass from the top:
+//              LDS histogram of the still-undecided candidates, then the first wave scans the
+//              256 bins (4 per lane, descending) and picks the digit that holds the k-th
+//              largest key.  The search stops as soon as every candidate left in that bin is
+//              needed (normally after 3-4 passes on real-valued scores); after all 8 passes the
+//              k-th key is known exactly and `need_eq` of its duplicates are taken, lowest
+//              index first.
+//   threshold: fp64 softmax over the full blocks (max, sum of exp, divide), S_j > tau.
+//   Either way an ordered compaction emits the ascending list: each thread owns a contiguous
+//   run of block ids, counts its hits, one work-group scan gives its offset.
 // ---------------------------------------------------------------------------------------
+constexpr int kSelectLdsBlocks = 8192;
+
 __device__ __forceinline__ uint64_t score_key(double s) {
   const uint64_t b = (uint64_t)__double_as_longlong(s);
   return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
@@ -104,18 +110,44 @@ __device__ __forceinline__ double wg_reduce_sum(double x, double* sm) {
   return (sm[0] + sm[1]) + (sm[2] + sm[3]);
 }
 
+// Exclusive prefix over the 256 threads of two per-thread counts (returns totals through tg/te).
+__device__ __forceinline__ void wg_exclusive_scan2(int a, int b, int* sm /* [2][4] */, int* ea, int* eb,
+                                                   int* ta, int* tb) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int ia = a, ib = b;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int xa = __shfl_up(ia, o), xb = __shfl_up(ib, o);
+    if (lane >= o) { ia += xa; ib += xb; }
+  }
+  __syncthreads();
+  if (lane == 63) { sm[wave] = ia; sm[4 + wave] = ib; }
+  __syncthreads();
+  int oa = 0, ob = 0, sa = 0, sb = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) { oa += sm[w]; ob += sm[4 + w]; }
+    sa += sm[w]; sb += sm[4 + w];
+  }
+  *ea = oa + ia - a;
+  *eb = ob + ib - b;
+  *ta = sa;
+  *tb = sb;
+}
+
+template <bool IN_LDS>
 __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
   __shared__ int hist[256];
-  __shared__ int scan[256];
-  __shared__ int wcnt[2][4];
-  __shared__ int digit_sel[2];
+  __shared__ int wcnt[8];
+  __shared__ int digit_sel[3];
   __shared__ double red[4];
 
   const int i = blockIdx.y, h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t grp = (int64_t)i * p.Hkv + h;
   int32_t* out = p.block_idx + grp * p.max_sel;
-  const double* sc = p.scores + grp * p.nb_max;
+  const double* sc_g = p.scores + grp * p.nb_max;
 
   int S = p.seqlens[i];
   S = S < 0 ? 0 : S;
@@ -124,9 +156,18 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   if (nb > p.nb_max) { nb = p.nb_max; nfull = nfull < nb ? nfull : nb; }
   const bool partial = nb > nfull;
 
+  const double* sc = sc_g;
+  if (IN_LDS) {
+    double* sl = reinterpret_cast<double*>(dyn_smem);
+    for (int j = tid; j < nfull; j += 256) sl[j] = sc_g[j];
+    __syncthreads();
+    sc = sl;
+  }
+
   // ---- decide what "selected" means -----------------------------------------------------
-  uint64_t T = ~0ull;      // top-k: key of the k-th largest score
-  int need_eq = 0;         // top-k: how many blocks equal to T are taken
+  uint64_t T = ~0ull;      // top-k: selected if key > T, or key == T among the first need_eq
+  int need_eq = 0;
+  bool take_ge = false;    // top-k, early exit: selected if key >= T
   int from_full = 0;
   bool force_last = partial;
   double m = 0.0, Z = 1.0;
@@ -142,7 +183,10 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     from_full = from_full > nfull ? nfull : from_full;
     force_last = partial && k > 0;
 
-    if (from_full > 0) {
+    if (from_full >= nfull) {
+      T = 0;               // every full block is taken
+      take_ge = true;
+    } else if (from_full > 0) {
       uint64_t prefix = 0, mask = 0;
       int remaining = from_full;
       for (int pass = 7; pass >= 0; --pass) {
@@ -154,28 +198,42 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
           if ((key & mask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 0xff)], 1);
         }
         __syncthreads();
-        // suffix sums over digits: scan[d] = number of candidates with digit >= d
-        scan[tid] = hist[tid];
-        __syncthreads();
-        for (int o = 1; o < 256; o <<= 1) {
-          int add = (tid + o < 256) ? scan[tid + o] : 0;
-          __syncthreads();
-          scan[tid] += add;
-          __syncthreads();
-        }
-        const int above = (tid < 255) ? scan[tid + 1] : 0;
-        if (above < remaining && remaining <= scan[tid]) {   // exactly one digit satisfies this
-          digit_sel[0] = tid;
-          digit_sel[1] = remaining - above;
+        if (wave == 0) {
+          // lane owns digits d0, d0-1, d0-2, d0-3 (descending); scan candidates from the top digit
+          const int d0 = 255 - 4 * lane;
+          const int c0 = hist[d0], c1 = hist[d0 - 1], c2 = hist[d0 - 2], c3 = hist[d0 - 3];
+          const int own = c0 + c1 + c2 + c3;
+          int incl = own;
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) {
+            const int x = __shfl_up(incl, o);
+            if (lane >= o) incl += x;
+          }
+          int above = incl - own;                     // candidates with a digit above d0
+          if (above < remaining && remaining <= incl) {   // true for exactly one lane
+            int dsel = d0, cnt = c0;
+            if (remaining > above + c0) {
+              above += c0; dsel = d0 - 1; cnt = c1;
+              if (remaining > above + c1) {
+                above += c1; dsel = d0 - 2; cnt = c2;
+                if (remaining > above + c2) { above += c2; dsel = d0 - 3; cnt = c3; }
+              }
+            }
+            digit_sel[0] = dsel;
+            digit_sel[1] = remaining - above;   // still needed from that digit's bin
+            digit_sel[2] = cnt;                 // candidates in that bin
+          }
         }
         __syncthreads();
         prefix |= (uint64_t)digit_sel[0] << shift;
         mask |= 0xffull << shift;
         remaining = digit_sel[1];
+        const bool all_of_bin = remaining == digit_sel[2];
         __syncthreads();
+        if (all_of_bin) { take_ge = true; break; }   // key >= prefix (low bits zero) is the selection
       }
       T = prefix;
-      need_eq = remaining;
+      need_eq = take_ge ? 0 : remaining;
     }
   } else {
     if (nfull > 0) {
@@ -188,46 +246,48 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     }
   }
 
-  // ---- ordered compaction -----------------------------------------------------------------
-  int run_gt = 0, run_eq = 0;
+  // ---- ordered compaction: thread t owns block ids [t*run, (t+1)*run) -----------------------
   const bool any_full = (p.mode == 0) ? (from_full > 0) : (nfull > 0);
+  int n = 0;
   if (any_full) {
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    for (int base = 0; base < nfull; base += 256) {
-      const int j = base + tid;
-      bool gt = false, eq = false;
-      if (j < nfull) {
-        const double s = sc[j];
-        if (p.mode == 0) {
-          const uint64_t key = score_key(s);
-          gt = key > T;
-          eq = key == T;
-        } else {
-          const double Sj = __ddiv_rn(exp(__dsub_rn(__dmul_rn(s, p.inv_sqrt_dg), m)), Z);
-          gt = Sj > p.threshold;
-        }
+    const int run = (nfull + 255) / 256;
+    const int j0 = tid * run;
+    const int j1 = (j0 + run < nfull) ? j0 + run : nfull;
+    auto classify = [&](int j, bool* gt, bool* eq) {
+      const double s = sc[j];
+      if (p.mode == 0) {
+        const uint64_t key = score_key(s);
+        *gt = take_ge ? key >= T : key > T;
+        *eq = !take_ge && key == T;
+      } else {
+        const double Sj = __ddiv_rn(exp(__dsub_rn(__dmul_rn(s, p.inv_sqrt_dg), m)), Z);
+        *gt = Sj > p.threshold;
+        *eq = false;
       }
-      const uint64_t bg = __ballot(gt), be = __ballot(eq);
-      const int pg = __popcll(bg & lt_mask), pe = __popcll(be & lt_mask);
-      __syncthreads();
-      if (lane == 0) { wcnt[0][wave] = __popcll(bg); wcnt[1][wave] = __popcll(be); }
-      __syncthreads();
-      int og = 0, oe = 0, tg = 0, te = 0;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const int a = wcnt[0][w], b = wcnt[1][w];
-        if (w < wave) { og += a; oe += b; }
-        tg += a; te += b;
-      }
-      const int eq_before = run_eq + oe + pe;
-      const bool take = gt || (eq && eq_before < need_eq);
-      const int pos = run_gt + og + pg + (eq_before < need_eq ? eq_before : need_eq);
-      if (take && pos < p.max_sel) out[pos] = j;
-      run_gt += tg;
-      run_eq += te;
+    };
+    int cg = 0, ce = 0;
+    for (int j = j0; j < j1; ++j) {
+      bool gt, eq;
+      classify(j, &gt, &eq);
+      cg += gt;
+      ce += eq;
     }
+    int og, oe, tg, te;
+    wg_exclusive_scan2(cg, ce, wcnt, &og, &oe, &tg, &te);
+    int eq_seen = oe;
+    int pos = og + (oe < need_eq ? oe : need_eq);
+    for (int j = j0; j < j1; ++j) {
+      bool gt, eq;
+      classify(j, &gt, &eq);
+      const bool take = gt || (eq && eq_seen < need_eq);
+      eq_seen += eq;
+      if (take) {
+        if (pos < p.max_sel) out[pos] = j;
+        ++pos;
+      }
+    }
+    n = tg + (te < need_eq ? te : need_eq);
   }
-  int n = run_gt + (run_eq < need_eq ? run_eq : need_eq);
   n = n < p.max_sel ? n : p.max_sel;
   if (force_last && n < p.max_sel) {
     if (tid == 0) out[n] = nb - 1;
@@ -245,7 +305,10 @@ hipError_t launch_gate_score(const GateParams& p, hipStream_t s) {
 
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
-  hipLaunchKernelGGL(seer_gate_select_kernel, grid, dim3(256), 0, s, p);
+  if (p.nb_max <= kSelectLdsBlocks)
+    hipLaunchKernelGGL(seer_gate_select_kernel<true>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
+  else
+    hipLaunchKernelGGL(seer_gate_select_kernel<false>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

@@ -52,6 +52,7 @@ hipError_t launch_gate_select(const GateParams& p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_merge(const DecodeParams& p, hipStream_t s);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int wgs, hipStream_t s);
 
 // ---- device helpers -------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -78,6 +79,49 @@ __device__ __forceinline__ int64_t block_offset(const DecodeParams& p, int i, in
     return page * p.stride_seq + (int64_t)hk * p.stride_head + (t0 % p.page_size) * p.stride_token;
   }
   return (int64_t)i * p.stride_seq + (int64_t)hk * p.stride_head + t0 * p.stride_token;
+}
+
+// fp32 -> bf16, round to nearest even.
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Final value of one output element from a (max, sum, unnormalised accumulator) triple in the
+// base-2 domain; also writes lse (natural log) from the thread that owns feature 0.
+__device__ __forceinline__ void store_output(const DecodeParams& p, int64_t row, int dd, float ma,
+                                             float l, float a) {
+  const float r = (l > 0.f) ? a / l : 0.f;
+  if (p.out_is_f32) reinterpret_cast<float*>(p.out)[row * kHeadDim + dd] = r;
+  else reinterpret_cast<uint16_t*>(p.out)[row * kHeadDim + dd] = f32_to_bf16_rne(r);
+  if (dd == 0 && p.lse) p.lse[row] = (l > 0.f) ? (ma + log2f(l)) * 0.6931471805599453f : -INFINITY;
+}
+
+// What a split kernel does with the merged (ma, l, a) of its slice for (head h, feature dd):
+// with a single split it is the final result, otherwise a partial for the merge kernel.
+__device__ __forceinline__ void emit_slice(const DecodeParams& p, int i, int hk, int split, int h,
+                                           int dd, float ma, float l, float a) {
+  const int64_t grp = (int64_t)i * p.Hkv + hk;
+  if (p.num_splits == 1) {
+    store_output(p, (int64_t)i * p.Hq + (int64_t)hk * p.g + h, dd, ma, l, a);
+  } else {
+    const int64_t pidx = (grp * p.num_splits + split) * p.g + h;
+    p.part_acc[pidx * kHeadDim + dd] = a;
+    if (dd == 0) {
+      p.part_ml[pidx * 2 + 0] = ma;
+      p.part_ml[pidx * 2 + 1] = l;
+    }
+  }
+}
+
+// A work-group whose slice starts past the end of the list has nothing to do, except that with a
+// single split it owns the (empty) result of the group.
+__device__ __forceinline__ void emit_empty_if_single_split(const DecodeParams& p, int i, int hk) {
+  if (p.num_splits != 1) return;
+  for (int o = threadIdx.x; o < p.g * kHeadDim; o += blockDim.x)
+    store_output(p, (int64_t)i * p.Hq + (int64_t)hk * p.g + o / kHeadDim, o % kHeadDim, -INFINITY, 0.f, 0.f);
 }
 
 }  // namespace seer

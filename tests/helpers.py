@@ -102,3 +102,43 @@ def pick_threshold(scores, seqlens, block_size, dg, target_keep):
     gaps = p[lo:hi + 1] - p[lo - 1:hi]
     c = lo + int(np.argmax(gaps))
     return float(0.5 * (p[c - 1] + p[c]))
+
+
+def oracle_decode_on_groups(inp, block_idx, nblk, groups):
+    """Oracle decode of a sample of (sequence, kv-head) groups of a large device-resident workload:
+    only the sampled groups' K/V (or, for a paged cache, the sampled heads' pools) are copied to
+    the host.  Returns (out [n,g,d], lse [n,g]) in the order of `groups` (flat ids i*Hkv + h)."""
+    w = inp.w
+    g, d = w.g, w.d
+    groups = np.asarray(groups)
+    bi, hi = groups // w.Hkv, groups % w.Hkv
+    tb = torch.as_tensor(bi)
+    q_s = torch.stack([inp.q[int(b), int(h) * g:(int(h) + 1) * g] for b, h in zip(bi, hi)]).cpu()
+    sl_s = inp.seqlens_cpu[tb].contiguous()
+    idx_c, cnt_c = cpu(block_idx), cpu(nblk)
+    if isinstance(idx_c, np.ndarray):
+        idx_c, cnt_c = torch.as_tensor(idx_c), torch.as_tensor(cnt_c)
+    idx_s = torch.stack([idx_c[int(b), int(h)] for b, h in zip(bi, hi)]).unsqueeze(1).contiguous()
+    cnt_s = torch.stack([cnt_c[int(b), int(h)] for b, h in zip(bi, hi)]).unsqueeze(1).contiguous()
+    n = len(groups)
+    if inp.page_table is None:
+        S_max = int(inp.seqlens_cpu.max())
+        ks = torch.stack([inp.k[int(b), int(h), :S_max] for b, h in zip(bi, hi)]).unsqueeze(1).cpu()
+        vs = torch.stack([inp.v[int(b), int(h), :S_max] for b, h in zip(bi, hi)]).unsqueeze(1).cpu()
+        return oracle.sparse_decode(q_s, KVLayout(ks, vs), sl_s, idx_s, cnt_s, w.block_size, w.scale)
+    out = np.zeros((n, g, d)); lse = np.zeros((n, g))
+    pt_all = inp.page_table.cpu()
+    for h in sorted(set(int(x) for x in hi)):
+        m = np.nonzero(hi == h)[0]
+        tm = torch.as_tensor(m)
+        kv = KVLayout(inp.k[:, h:h + 1].cpu(), inp.v[:, h:h + 1].cpu(), pt_all[tb[tm]].contiguous(), inp.page_size)
+        o, l = oracle.sparse_decode(q_s[tm], kv, sl_s[tm], idx_s[tm], cnt_s[tm], w.block_size, w.scale)
+        out[m], lse[m] = o, l
+    return out, lse
+
+
+def gather_groups(t, w, groups, per_head):
+    """Rows of a [B,Hq,...] (per_head=g) or [B,Hkv,...] (per_head=1) device tensor for sampled groups."""
+    groups = np.asarray(groups)
+    bi, hi = groups // w.Hkv, groups % w.Hkv
+    return torch.stack([t[int(b), int(h) * per_head:(int(h) + 1) * per_head] for b, h in zip(bi, hi)])
