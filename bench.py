@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=128, help="groups the CPU oracle is timed on")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (reference for hardware counters)")
     ap.add_argument("--dense-steps", type=int, default=5, help="timed dense flash-decode steps (0 = skip the dense baseline)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -179,6 +181,14 @@ def main():
     stream_gbps = probe_bytes / (tot_p / n_p * 1e-3) / 1e9
     seer.profile_reset()
 
+    if args.calibrate_copy_mib > 0:
+        a = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        b_ = torch.empty_like(a)
+        for _ in range(3):
+            b_.copy_(a)
+        torch.cuda.synchronize()
+        del a, b_
+
     # ---- byte model from the selection the gate actually made (query set 0)
     seer.gate_select(qgs[0], base.kc, base.seqlens, bs, budget_tokens=w.budget_tokens, budget_blocks=base.budget_blocks,
                      max_sel=max_sel, block_idx=idxs[0], nblk=cnts[0], workspace=ws_gate)
@@ -191,6 +201,13 @@ def main():
     split_us = kern["decode_split"]["avg_us"]
     achieved = ab["decode"] / (split_us * 1e-6) / 1e9
     merge_us = kern["decode_merge"]["avg_us"] or 0.0
+
+    traffic = None
+    try:     # hardware-counter traffic of this kernel on this workload, if a committed measurement exists
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            traffic = json.load(f).get(w.name, {}).get("decode_split_bytes")
+    except OSError:
+        pass
 
     result = {
         "metric": "sparse decode attention tokens/s + achieved HBM GB/s (% peak) at 90% sparsity",
@@ -207,7 +224,7 @@ def main():
                    "realised_sparsity": sparsity, "query_sets": R, "kv_copies": kv_copies,
                    "decode_impl": {0: "auto(mfma)", 1: "valu", 2: "mfma"}[args.impl]},
         "roofline": {"bound": "hbm", "kernel": "seer_decode_split (sparse)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": ab["decode"], "avg_kernel_us": split_us},
         "hbm_GBps_selected_kv": achieved, "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "kernels_avg_us": {k: v["avg_us"] for k, v in kern.items()},
