@@ -84,6 +84,8 @@ def main():
     seer.set_knob(0, args.impl)
     seer.set_knob(1, args.splits)
     w = synth.CONFIGS[args.workload]
+    ragged = w.seqlen_dist != "fixed" or w.budget_tokens == 0      # lists of very different lengths
+    seer.set_knob(2, 1 if ragged else 0)
     log(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} paged={w.paged}")
 
     # ---- inputs: one KV cache (or several, to defeat the 256 MB Infinity Cache on small configs)
@@ -222,7 +224,7 @@ def main():
                                f"max_sel {max_sel}, {'paged' if w.paged else 'contiguous'} KV",
                    "step": "gate score + top-k select + sparse split-K decode + LSE merge",
                    "realised_sparsity": sparsity, "query_sets": R, "kv_copies": kv_copies,
-                   "decode_impl": {0: "auto(mfma)", 1: "valu", 2: "mfma"}[args.impl]},
+                   "decode_impl": {0: "auto(mfma)", 1: "valu", 2: "mfma"}[args.impl], "ragged_lists_hint": ragged},
         "roofline": {"bound": "hbm", "kernel": "seer_decode_split (sparse)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": ab["decode"], "avg_kernel_us": split_us},

@@ -88,7 +88,8 @@ seer_status seer_gate_workspace_bytes(int B, int Hkv, int nb_max, size_t* bytes 
 
 /*
  * Bytes of workspace seer_sparse_decode / seer_dense_decode need.  max_blocks is max_sel for
- * the sparse call and the largest number of blocks of any sequence for the dense call.
+ * the sparse call and the largest number of blocks of any sequence for the dense call.  The size
+ * covers every split plan the knobs can produce, so it stays valid when a knob changes.
  */
 seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_blocks,
                                         size_t* bytes /* host, out */);
@@ -166,8 +167,15 @@ seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void*
  * Tuning knobs (process-wide, host call).  Unknown knobs return SEER_ERR_UNSUPPORTED.
  *   SEER_KNOB_DECODE_IMPL    0 = auto, 1 = VALU kernel, 2 = MFMA kernel
  *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
+ *   SEER_KNOB_DECODE_RAGGED  0 = the lists of a call have about equal lengths (token budget on
+ *                            long sequences; default), 1 = very different lengths (per-sequence
+ *                            budgets, threshold mode, mixed sequence lengths): shorter slices
  */
-typedef enum seer_knob { SEER_KNOB_DECODE_IMPL = 0, SEER_KNOB_DECODE_SPLITS = 1 } seer_knob;
+typedef enum seer_knob {
+  SEER_KNOB_DECODE_IMPL = 0,
+  SEER_KNOB_DECODE_SPLITS = 1,
+  SEER_KNOB_DECODE_RAGGED = 2
+} seer_knob;
 seer_status seer_set_knob(int knob, int value);
 seer_status seer_get_knob(int knob, int* value /* host, out */);
 

@@ -18,6 +18,7 @@ SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
+KNOB_DECODE_RAGGED = 2
 KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read")
 
 
@@ -49,10 +50,11 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
+    path = os.environ.get("SEER_LIB", _LIB_PATH)     # SEER_LIB: an alternative build of the same library
+    if path == _LIB_PATH and not os.path.exists(_LIB_PATH):
         from . import build as _build
         _build.build()
-    lib = ctypes.CDLL(_LIB_PATH)
+    lib = ctypes.CDLL(path)
     c_int, c_i64, c_vp, c_sz = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
     lib.seer_version.restype = c_int
     lib.seer_status_string.restype = ctypes.c_char_p

@@ -24,15 +24,16 @@ def flags() -> list:
             "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False, extra: list | None = None) -> str:
+def build(verbose: bool = False, extra: list | None = None, out: str | None = None) -> str:
     """Compile every kernel for gfx950 and link the shared library (always recompiles)."""
-    tmp = LIB + f".tmp{os.getpid()}"
+    lib = out or LIB
+    tmp = lib + f".tmp{os.getpid()}"
     cmd = [hipcc()] + flags() + (extra or []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":

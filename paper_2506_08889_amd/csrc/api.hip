@@ -14,6 +14,7 @@ namespace {
 
 int g_knob_impl = 0;
 int g_knob_splits = 0;
+int g_knob_ragged = 0;
 
 struct ProfEvent { int cls; hipEvent_t a, b; };
 bool g_prof_on = false;
@@ -39,20 +40,36 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // How the block list is cut: num_splits slices of blocks_per_split list entries each (the
 // partition runs over the list capacity, not over the blocks of the sequence, Sec. 3.3).
-// The split kernels keep 2 work-groups per CU resident; the plan aims at one resident round of
-// work-groups (measured best on MI355X) with at least 4 list entries per slice.
-void plan_splits(int B, int Hkv, int max_blocks, int* num_splits, int* blocks_per_split) {
+// The split kernels keep 2 work-groups per CU resident.  For lists of equal length one resident
+// round of work-groups is best (measured on MI355X), with at least 4 list entries per slice.
+// Lists of very different lengths (SEER_KNOB_DECODE_RAGGED) get slices of about 2048 tokens so
+// that the longest list is spread over many work-groups; equal-length lists lose ~5 % to that,
+// hence the opt-in.
+constexpr long kMinSliceBlocks = 4;    // at least one block per wave of a work-group
+constexpr long kMaxSplits = 256;
+
+long max_splits_for(int max_blocks) {
+  long m = (max_blocks + kMinSliceBlocks - 1) / kMinSliceBlocks;
+  return m < 1 ? 1 : (m > kMaxSplits ? kMaxSplits : m);
+}
+
+void plan_splits(int B, int Hkv, int max_blocks, int block_size, int* num_splits, int* blocks_per_split) {
   const long groups = (long)B * Hkv;
   const long slots = (long)cu_count() * 2;
   long ns;
-  if (g_knob_splits > 0) ns = g_knob_splits;
-  else if (groups >= slots) ns = 1;
-  else ns = (slots + groups / 2) / groups;
-  const long min_len = 4;   // at least one block per wave of a work-group
-  long max_ns = (max_blocks + min_len - 1) / min_len;
-  if (max_ns < 1) max_ns = 1;
-  if (ns > max_ns) ns = max_ns;
-  if (ns > 256) ns = 256;
+  if (g_knob_splits > 0) {
+    ns = g_knob_splits;
+  } else {
+    ns = groups >= slots ? 1 : (slots + groups / 2) / groups;
+    if (g_knob_ragged) {
+      long len_r = 2048 / block_size;
+      if (len_r < kMinSliceBlocks) len_r = kMinSliceBlocks;
+      const long ns_r = (max_blocks + len_r - 1) / len_r;
+      if (ns_r > ns) ns = ns_r;
+    }
+  }
+  const long cap = max_splits_for(max_blocks);
+  if (ns > cap) ns = cap;
   if (ns < 1) ns = 1;
   long len = (max_blocks + ns - 1) / ns;
   if (len < 1) len = 1;
@@ -62,7 +79,8 @@ void plan_splits(int B, int Hkv, int max_blocks, int* num_splits, int* blocks_pe
   *blocks_per_split = (int)len;
 }
 
-size_t decode_ws_bytes(int B, int Hkv, int g, int num_splits) {
+// Workspace for the largest plan any knob setting can produce, so a size queried once stays valid.
+size_t decode_ws_bytes(int B, int Hkv, int g, long num_splits) {
   const size_t parts = (size_t)B * Hkv * num_splits * g;
   return align_up(parts * seer::kHeadDim * sizeof(float), 256) + align_up(parts * 2 * sizeof(float), 256);
 }
@@ -111,8 +129,8 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
     if (kv->page_size <= 0 || kv->max_pages <= 0 || kv->page_size % block_size != 0) return SEER_ERR_SHAPE;
   }
   int ns, len;
-  plan_splits(B, Hkv, max_blocks, &ns, &len);
-  const size_t need = decode_ws_bytes(B, Hkv, g, ns);
+  plan_splits(B, Hkv, max_blocks, block_size, &ns, &len);
+  const size_t need = decode_ws_bytes(B, Hkv, g, max_splits_for(max_blocks));
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SEER_ERR_WORKSPACE;
 
@@ -188,9 +206,7 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
   if (!bytes) return SEER_ERR_NULL;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || Hq % Hkv) return SEER_ERR_SHAPE;
   if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup) return SEER_ERR_UNSUPPORTED;
-  int ns, len;
-  plan_splits(B, Hkv, max_blocks, &ns, &len);
-  *bytes = decode_ws_bytes(B, Hkv, Hq / Hkv, ns);
+  *bytes = decode_ws_bytes(B, Hkv, Hq / Hkv, max_splits_for(max_blocks));
   return SEER_OK;
 }
 
@@ -293,6 +309,10 @@ seer_status seer_set_knob(int knob, int value) {
       if (value < 0) return SEER_ERR_SHAPE;
       g_knob_splits = value;
       return SEER_OK;
+    case SEER_KNOB_DECODE_RAGGED:
+      if (value < 0 || value > 1) return SEER_ERR_SHAPE;
+      g_knob_ragged = value;
+      return SEER_OK;
     default: return SEER_ERR_UNSUPPORTED;
   }
 }
@@ -302,6 +322,7 @@ seer_status seer_get_knob(int knob, int* value) {
   switch (knob) {
     case SEER_KNOB_DECODE_IMPL: *value = g_knob_impl; return SEER_OK;
     case SEER_KNOB_DECODE_SPLITS: *value = g_knob_splits; return SEER_OK;
+    case SEER_KNOB_DECODE_RAGGED: *value = g_knob_ragged; return SEER_OK;
     default: return SEER_ERR_UNSUPPORTED;
   }
 }

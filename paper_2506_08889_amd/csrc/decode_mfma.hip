@@ -64,19 +64,53 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   // 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256];
 
-  const int split = blockIdx.x, hk = blockIdx.y, i = blockIdx.z;
+  int split, hk, i;
+  decode_wg_coords(p, &split, &hk, &i);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
   const int g = p.g;
 
+  const int bs = p.block_size;
+  const int64_t grp = (int64_t)i * p.Hkv + hk;
+  const int begin = split * p.blocks_per_split;
+  const int32_t* list = p.block_idx ? p.block_idx + grp * p.max_blocks : nullptr;
+  // Entries of this slice that exist in memory whatever the group's count turns out to be.
+  const int slice_cap = (begin + p.blocks_per_split < p.max_blocks) ? begin + p.blocks_per_split : p.max_blocks;
+
+  // ---- block descriptors ---------------------------------------------------------------------
+  // Lane e of a 64-entry chunk holds list entry begin + 64*chunk + e.  A chunk is fetched in two
+  // stages ahead of its use (list entry, then its page id), each issued one loop iteration apart,
+  // so neither the index -> address dependency nor the page-table lookup is ever waited for in the
+  // main loop; the first chunk's list entries are requested before the group's count is known.
+  int pf_chunk = -1, pf_stage = 0, j_pf = -1, pg_pf = 0;
+  auto pf_stage1 = [&](int chunk) {
+    pf_chunk = chunk;
+    pf_stage = 1;
+    const int pe = begin + chunk * 64 + lane;
+    j_pf = -1;
+    if (pe < slice_cap) j_pf = list ? list[pe] : pe;
+  };
+  auto pf_stage2 = [&]() {
+    pf_stage = 2;
+    pg_pf = 0;
+    if (p.page_table) {
+      int64_t pi = ((int64_t)j_pf * bs) / p.page_size;
+      pi = pi < 0 ? 0 : (pi >= p.max_pages ? p.max_pages - 1 : pi);    // always a valid table slot
+      pg_pf = p.page_table[(int64_t)i * p.max_pages + pi];
+    }
+  };
+  pf_stage1(0);
+
   int S = p.seqlens[i];
   S = S < 0 ? 0 : S;
-  const int bs = p.block_size;
   const int nb = (S + bs - 1) / bs;
-  const int64_t grp = (int64_t)i * p.Hkv + hk;
-  const int32_t* list;
-  const int n = group_list(p, grp, nb, &list);
-  const int begin = split * p.blocks_per_split;
+  int n;
+  if (p.block_idx) {
+    n = p.nblk[grp];
+    n = n < 0 ? 0 : (n < p.max_blocks ? n : p.max_blocks);
+  } else {
+    n = nb < p.max_blocks ? nb : p.max_blocks;
+  }
   if (begin >= n) {
     emit_empty_if_single_split(p, i, hk);
     return;
@@ -85,6 +119,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   const int hpb = bs >> 5;                 // half-blocks (32 tokens) per block
   const int nh = (end - begin) * hpb;      // half-blocks in this slice
   const int64_t st = ROWS128 ? (int64_t)kHeadDim : p.stride_token;
+  pf_stage2();
 
   // ---- Q^T operand: head n16 (zero rows for the padding heads) ---------------------------
   uint4 qb[4];
@@ -96,10 +131,27 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
           p.q + ((int64_t)i * p.Hq + (int64_t)hk * g + n16) * kHeadDim + kk * 32 + q4 * 8);
   }
 
-  // ---- block descriptors: lane e of a 64-entry chunk holds list entry begin + 64*chunk + e --
   int loaded_chunk = -1;
   int64_t d_off = 0;
   int d_ntok = 0;
+  auto finalize_chunk = [&](int chunk) {
+    if (pf_chunk != chunk) pf_stage1(chunk);
+    if (pf_stage < 2) pf_stage2();
+    const int pe = begin + chunk * 64 + lane;
+    const int j = j_pf;
+    bool ok = pe < end && j >= 0 && j < nb;
+    if (ok && p.page_table) ok = ((int64_t)j * bs) / p.page_size < p.max_pages;
+    d_off = 0;
+    d_ntok = 0;
+    if (ok) {
+      const int64_t t0 = (int64_t)j * bs;
+      d_off = p.page_table ? (int64_t)pg_pf * p.stride_seq + (int64_t)hk * p.stride_head + (t0 % p.page_size) * p.stride_token
+                           : (int64_t)i * p.stride_seq + (int64_t)hk * p.stride_head + t0 * p.stride_token;
+      d_ntok = (S - j * bs < bs) ? S - j * bs : bs;
+    }
+    loaded_chunk = chunk;
+  };
+
   int hb = wave;
   auto advance = [&]() -> HalfBlock {
     HalfBlock r;
@@ -109,19 +161,10 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
       const int e = hb / hpb, half = hb - e * hpb;
       const int chunk = e >> 6;
       if (chunk != loaded_chunk) {
-        loaded_chunk = chunk;
-        const int pe = begin + chunk * 64 + lane;
-        d_ntok = 0;
-        d_off = 0;
-        if (pe < end) {
-          const int j = list ? list[pe] : pe;
-          bool ok = j >= 0 && j < nb;
-          if (ok && p.page_table) ok = ((int64_t)j * bs) / p.page_size < p.max_pages;
-          if (ok) {
-            d_off = block_offset(p, i, hk, j);
-            d_ntok = (S - j * bs < bs) ? S - j * bs : bs;
-          }
-        }
+        finalize_chunk(chunk);
+        if (begin + (chunk + 1) * 64 < end) pf_stage1(chunk + 1);
+      } else if (pf_chunk > loaded_chunk && pf_stage == 1) {
+        pf_stage2();
       }
       const int src = e & 63;
       const int nt_blk = __shfl(d_ntok, src);
@@ -305,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 }
 
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s) {
-  dim3 grid(p.num_splits, p.Hkv, p.B);
+  const dim3 grid = decode_grid(p);
   if (p.stride_token == kHeadDim)
     hipLaunchKernelGGL(seer_decode_split_mfma_kernel<true>, grid, dim3(256), 0, s, p);
   else

@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
   __shared__ float sm_acc[4][G][kHeadDim];
   __shared__ float sm_ml[4][G][2];
 
-  const int split = blockIdx.x, hk = blockIdx.y, i = blockIdx.z;
+  int split, hk, i;
+  decode_wg_coords(p, &split, &hk, &i);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int slot = lane >> 4, c = lane & 15;
 
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
 }
 
 hipError_t launch_decode_split_valu(const DecodeParams& p, hipStream_t s) {
-  dim3 grid(p.num_splits, p.Hkv, p.B);
+  const dim3 grid = decode_grid(p);
   dim3 block(256);
   switch (p.g) {
 #define SEER_CASE(G) \

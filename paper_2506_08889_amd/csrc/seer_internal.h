@@ -58,6 +58,19 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int wgs
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// Work-group -> (split, kv head, sequence).  Grid (Hkv, B, num_splits): the split index is the
+// slowest dimension, so consecutive work-group ids are consecutive (sequence, kv-head) groups of
+// the same split.  Work-groups are handed to the 8 XCDs round-robin by linear id, so every XCD
+// gets an equal share of every split; with the split fastest, XCD k would receive only split k
+// of every group, and the later splits are empty for all but the longest lists (measured on the
+// variable-length workloads: 1.75x slower).
+__device__ __forceinline__ void decode_wg_coords(const DecodeParams& p, int* split, int* hk, int* i) {
+  *hk = blockIdx.x;
+  *i = blockIdx.y;
+  *split = blockIdx.z;
+}
+inline dim3 decode_grid(const DecodeParams& p) { return dim3(p.Hkv, p.B, p.num_splits); }
+
 // Number of list entries of a group and the list itself (nullptr: dense, entry p is block p).
 __device__ __forceinline__ int group_list(const DecodeParams& p, int64_t grp, int nb,
                                           const int32_t** list) {

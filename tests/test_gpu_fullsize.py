@@ -26,6 +26,7 @@ def run_full(name, n_sample, mode=seer.SELECT_TOPK, keep=None, block_size=None):
     seer.set_knob(0, 0)
     seer.set_knob(1, 0)
     w = synth.CONFIGS[name]
+    seer.set_knob(2, 1 if (w.seqlen_dist != "fixed" or w.budget_tokens == 0) else 0)   # as bench.py does
     if block_size:
         w = synth.scaled(w, block_size=block_size)
     print(f"[full] {w.name} b={w.block_size} mode={mode}", flush=True)

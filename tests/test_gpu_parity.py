@@ -21,11 +21,11 @@ IMPLS = {"valu": 1, "mfma": 2}
 
 @pytest.fixture(autouse=True)
 def _reset_knobs():
-    seer.set_knob(0, 0)
-    seer.set_knob(1, 0)
+    for k in (0, 1, 2):
+        seer.set_knob(k, 0)
     yield
-    seer.set_knob(0, 0)
-    seer.set_knob(1, 0)
+    for k in (0, 1, 2):
+        seer.set_knob(k, 0)
 
 
 def gpu_gate(inp, mode=seer.SELECT_TOPK, threshold=0.0, max_sel=None):
@@ -41,7 +41,7 @@ def gpu_decode(inp, block_idx, nblk, out_dtype):
                               page_table=inp.page_table, page_size=inp.page_size, out_dtype=out_dtype)
 
 
-def run_gate_and_decode(w, impls=("valu", "mfma"), splits=(0,)):
+def run_gate_and_decode(w, impls=("valu", "mfma"), splits=(0,), ragged=0):
     print(f"[case] {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} seed={w.seed}", flush=True)
     inp = synth.make_inputs(w, DEV)
     ref_idx, ref_cnt = oracle_gate(inp)
@@ -55,6 +55,7 @@ def run_gate_and_decode(w, impls=("valu", "mfma"), splits=(0,)):
         seer.set_knob(0, IMPLS[impl])
         for ns in splits:
             seer.set_knob(1, ns)
+            seer.set_knob(2, ragged)
             for dt, tight in ((torch.float32, True), (torch.bfloat16, False)):
                 print(f"[decode] {w.name} impl={impl} splits={ns} out={dt}", flush=True)
                 out, lse = gpu_decode(inp, idx, cnt, dt)
@@ -77,7 +78,7 @@ def test_c2_shape_scaled():
 
 def test_c3_shape_scaled_paged_varlen_outliers():
     w = synth.scaled(synth.CONFIGS["c3"], B=5, seqlen_range=(900, 6000))
-    inp, idx, cnt, _, _ = run_gate_and_decode(w, splits=(0, 5))
+    inp, idx, cnt, _, _ = run_gate_and_decode(w, splits=(0, 5), ragged=1)
     # the ragged tail really is exercised
     assert (inp.seqlens_cpu % w.block_size != 0).any()
     nb = (inp.seqlens_cpu + w.block_size - 1) // w.block_size
@@ -94,7 +95,7 @@ def test_c4_shape_scaled_group_of_five():
 @pytest.mark.parametrize("bs", [64, 128])
 def test_c5_shape_scaled_topk_and_threshold(bs):
     w = synth.scaled(synth.CONFIGS["c5"], B=6, block_size=bs, seqlen_range=(300, 9000), name=f"c5_b{bs}")
-    inp, idx, cnt, _, _ = run_gate_and_decode(w, impls=("mfma",))
+    inp, idx, cnt, _, _ = run_gate_and_decode(w, impls=("mfma",), ragged=1)
     # threshold mode at several sparsity levels, thresholds placed between adjacent probabilities
     _, _, scores = oracle_gate(inp, return_scores=True)
     for keep in (0.5, 0.25, 0.10, 0.05):
