@@ -189,12 +189,12 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     const uint16_t* base = p.k + b.off + n16 * 8;
     if (b.ntok == 32) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) kr[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(4 * u + q4) * st);
+      for (int u = 0; u < 8; ++u) kr[u] = load_stream16(base + (int64_t)(4 * u + q4) * st);
     } else {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         kr[u] = make_uint4(0, 0, 0, 0);
-        if (4 * u + q4 < b.ntok) kr[u] = *reinterpret_cast<const uint4*>(base + (int64_t)(4 * u + q4) * st);
+        if (4 * u + q4 < b.ntok) kr[u] = load_stream16(base + (int64_t)(4 * u + q4) * st);
       }
     }
   };
@@ -204,14 +204,14 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int row = (j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4);
-        vr[j] = *reinterpret_cast<const uint4*>(base + (int64_t)row * st);
+        vr[j] = load_stream16(base + (int64_t)row * st);
       }
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int row = (j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4);
         vr[j] = make_uint4(0, 0, 0, 0);
-        if (row < b.ntok) vr[j] = *reinterpret_cast<const uint4*>(base + (int64_t)row * st);
+        if (row < b.ntok) vr[j] = load_stream16(base + (int64_t)row * st);
       }
     }
   };

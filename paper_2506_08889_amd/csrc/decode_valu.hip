@@ -69,8 +69,8 @@ __global__ __launch_bounds__(256) void seer_decode_split_valu_kernel(DecodeParam
     const uint16_t* kb = p.k + off + c * 8;
     const uint16_t* vb = p.v + off + c * 8;
     for (int tt = wave * 4 + slot; tt < ntok; tt += 16) {
-      const uint4 kr = *reinterpret_cast<const uint4*>(kb + (int64_t)tt * p.stride_token);
-      const uint4 vr = *reinterpret_cast<const uint4*>(vb + (int64_t)tt * p.stride_token);
+      const uint4 kr = load_stream16(kb + (int64_t)tt * p.stride_token);
+      const uint4 vr = load_stream16(vb + (int64_t)tt * p.stride_token);
       const uint32_t kw[4] = {kr.x, kr.y, kr.z, kr.w};
       const uint32_t vw[4] = {vr.x, vr.y, vr.z, vr.w};
       float kf[8], vf[8];

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
     jj[it] = j0 + wave * 16 + it * 4 + slot;
     kr[it] = make_uint4(0, 0, 0, 0);
     if (jj[it] < nfull)
-      kr[it] = *reinterpret_cast<const uint4*>(base + (int64_t)jj[it] * p.kc_stride_block + c * 8);
+      kr[it] = load_stream16(base + (int64_t)jj[it] * p.kc_stride_block + c * 8);
   }
 #pragma unroll
   for (int it = 0; it < 4; ++it) {

@@ -12,12 +12,12 @@ __global__ __launch_bounds__(256) void seer_stream_read_kernel(const uint4* __re
   for (; idx + 7 * stride < n16; idx += 8 * stride) {
     uint4 r[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) r[u] = src[idx + u * stride];
+    for (int u = 0; u < 8; ++u) r[u] = load_stream16(reinterpret_cast<const uint16_t*>(src + idx + u * stride));
 #pragma unroll
     for (int u = 0; u < 8; ++u) { acc.x ^= r[u].x; acc.y ^= r[u].y; acc.z ^= r[u].z; acc.w ^= r[u].w; }
   }
   for (; idx < n16; idx += stride) {
-    const uint4 r = src[idx];
+    const uint4 r = load_stream16(reinterpret_cast<const uint16_t*>(src + idx));
     acc.x ^= r.x; acc.y ^= r.y; acc.z ^= r.z; acc.w ^= r.w;
   }
   // practically never true; keeps the loads alive

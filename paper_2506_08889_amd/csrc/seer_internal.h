@@ -58,6 +58,22 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int wgs
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// 16-byte load of data that is read exactly once per call (K/V rows, compression-cache rows).
+// Marked non-temporal: on MI355X this raised the sparse decode kernel from 6.0 to 6.8 TB/s, the
+// streamed rows no longer displace each other through the cache hierarchy on their way in.
+#ifndef SEER_NT_LOADS
+#define SEER_NT_LOADS 1
+#endif
+__device__ __forceinline__ uint4 load_stream16(const uint16_t* ptr) {
+#if SEER_NT_LOADS
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(ptr));
+  return make_uint4(r[0], r[1], r[2], r[3]);
+#else
+  return *reinterpret_cast<const uint4*>(ptr);
+#endif
+}
+
 // Work-group -> (split, kv head, sequence).  Grid (Hkv, B, num_splits): the split index is the
 // slowest dimension, so consecutive work-group ids are consecutive (sequence, kv-head) groups of
 // the same split.  Work-groups are handed to the 8 XCDs round-robin by linear id, so every XCD
