@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--kv-copies", type=int, default=0, help="independent KV caches cycled (0 = auto)")
     ap.add_argument("--impl", type=int, default=0, help="0 auto, 1 VALU kernel, 2 MFMA kernel")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--gate-impl", type=int, default=0, help="0 auto, 1 two kernels, 2 fused")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=128, help="groups the CPU oracle is timed on")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
@@ -86,6 +87,7 @@ def main():
     w = synth.CONFIGS[args.workload]
     ragged = w.seqlen_dist != "fixed" or w.budget_tokens == 0      # lists of very different lengths
     seer.set_knob(2, 1 if ragged else 0)
+    seer.set_knob(3, args.gate_impl)
     log(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} paged={w.paged}")
 
     # ---- inputs: one KV cache (or several, to defeat the 256 MB Infinity Cache on small configs)
@@ -231,7 +233,7 @@ def main():
         "hbm_GBps_selected_kv": achieved, "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBPS,
         "kernels_avg_us": {k: v["avg_us"] for k, v in kern.items()},
         "ms_per_step_with_events": ms_step_prof,
-        "gate_GBps": (ab["gate"] / (kern["gate_score"]["avg_us"] * 1e-6) / 1e9) if kern["gate_score"]["avg_us"] else None,
+        "gate_GBps": ab["gate"] / (((kern["gate_score"]["avg_us"] or 0.0) + (kern["gate_select"]["avg_us"] or 0.0)) * 1e-6) / 1e9,
         "stream_read_GBps": stream_gbps,
         "dense": None, "speedup_vs_dense": None,
         "paper_context": "paper: up to 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware, not a target)",

@@ -170,11 +170,14 @@ seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void*
  *   SEER_KNOB_DECODE_RAGGED  0 = the lists of a call have about equal lengths (token budget on
  *                            long sequences; default), 1 = very different lengths (per-sequence
  *                            budgets, threshold mode, mixed sequence lengths): shorter slices
+ *   SEER_KNOB_GATE_IMPL      0 = auto, 1 = score kernel + select kernel, 2 = one fused kernel
+ *                            (when the cache has at most 8192 blocks per sequence)
  */
 typedef enum seer_knob {
   SEER_KNOB_DECODE_IMPL = 0,
   SEER_KNOB_DECODE_SPLITS = 1,
-  SEER_KNOB_DECODE_RAGGED = 2
+  SEER_KNOB_DECODE_RAGGED = 2,
+  SEER_KNOB_GATE_IMPL = 3
 } seer_knob;
 seer_status seer_set_knob(int knob, int value);
 seer_status seer_get_knob(int knob, int* value /* host, out */);

@@ -19,6 +19,7 @@ SELECT_THRESHOLD = 1
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
 KNOB_DECODE_RAGGED = 2
+KNOB_GATE_IMPL = 3
 KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read")
 
 

@@ -15,6 +15,7 @@ namespace {
 int g_knob_impl = 0;
 int g_knob_splits = 0;
 int g_knob_ragged = 0;
+int g_knob_gate = 0;
 
 struct ProfEvent { int cls; hipEvent_t a, b; };
 bool g_prof_on = false;
@@ -258,6 +259,18 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
+  // A wide score kernel (every CU streams cache rows) followed by the select kernel is the faster
+  // form at scale (measured: c4 61 us vs 66 us fused).  The fused kernel (one work-group per group
+  // computes its scores straight into LDS, then selects) saves a launch and wins only when the
+  // whole compression cache is tiny and the step is launch-latency bound.
+  bool fused = seer::gate_fused_possible(p) && (size_t)B * Hkv * nb_max * Dg * 2 <= ((size_t)1 << 20);
+  if (g_knob_gate == 1) fused = false;
+  if (g_knob_gate == 2) fused = seer::gate_fused_possible(p);
+  if (fused) {
+    Timed t(SEER_KERNEL_GATE_SELECT, s);
+    e = seer::launch_gate_fused(p, s);
+    return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+  }
   {
     Timed t(SEER_KERNEL_GATE_SCORE, s);
     e = seer::launch_gate_score(p, s);
@@ -313,6 +326,10 @@ seer_status seer_set_knob(int knob, int value) {
       if (value < 0 || value > 1) return SEER_ERR_SHAPE;
       g_knob_ragged = value;
       return SEER_OK;
+    case SEER_KNOB_GATE_IMPL:
+      if (value < 0 || value > 2) return SEER_ERR_SHAPE;
+      g_knob_gate = value;
+      return SEER_OK;
     default: return SEER_ERR_UNSUPPORTED;
   }
 }
@@ -323,6 +340,7 @@ seer_status seer_get_knob(int knob, int* value) {
     case SEER_KNOB_DECODE_IMPL: *value = g_knob_impl; return SEER_OK;
     case SEER_KNOB_DECODE_SPLITS: *value = g_knob_splits; return SEER_OK;
     case SEER_KNOB_DECODE_RAGGED: *value = g_knob_ragged; return SEER_OK;
+    case SEER_KNOB_GATE_IMPL: *value = g_knob_gate; return SEER_OK;
     default: return SEER_ERR_UNSUPPORTED;
   }
 }

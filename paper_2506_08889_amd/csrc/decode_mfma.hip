@@ -1,6 +1,6 @@
 // Block-sparse flash-decoding, split-K main kernel, MFMA formulation for gfx950 (Sec. 3.3).
 //
-// Grid (num_splits, Hkv, B): a work-group owns one (sequence, kv head) query group and one
+// Grid (Hkv, B, num_splits): a work-group owns one (sequence, kv head) query group and one
 // contiguous slice of its selected-block list (the list is partitioned over its capacity,
 // not over the blocks of the sequence).  Inside the work-group the 4 wavefronts are fully
 // independent: wave w takes the 32-token half-blocks w, w+4, ... of the slice, keeps its own

@@ -1,6 +1,6 @@
 // Block-sparse flash-decoding, split-K main kernel, vector-ALU formulation (Sec. 3.3).
 //
-// Grid (num_splits, Hkv, B): a work-group owns one (sequence, kv head) query group and one
+// Grid (Hkv, B, num_splits): a work-group owns one (sequence, kv head) query group and one
 // contiguous slice of its selected-block list.  A K or V row is 256 bytes = 16 lanes x one
 // 128-bit load, so a wavefront reads 4 token rows per load instruction, fully coalesced; the
 // 4 waves x 4 row slots form 16 independent online-softmax streams that are merged once at

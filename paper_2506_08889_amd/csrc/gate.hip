@@ -135,7 +135,10 @@ __device__ __forceinline__ void wg_exclusive_scan2(int a, int b, int* sm /* [2][
   *tb = sb;
 }
 
-template <bool IN_LDS>
+// SRC: 0 = scores stay in global memory (cache longer than the LDS budget), 1 = scores of the
+// score kernel are copied into LDS, 2 = fused: this kernel computes the scores itself, straight
+// into LDS (one launch, no score workspace traffic).
+template <int SRC>
 __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
   __shared__ int hist[256];
@@ -157,9 +160,53 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   const bool partial = nb > nfull;
 
   const double* sc = sc_g;
-  if (IN_LDS) {
+  if (SRC == 1) {
     double* sl = reinterpret_cast<double*>(dyn_smem);
     for (int j = tid; j < nfull; j += 256) sl[j] = sc_g[j];
+    __syncthreads();
+    sc = sl;
+  }
+  if (SRC == 2) {
+    // Stream the group's cache rows: 16 lanes per 256-byte row, 4 rows per wave and load, 8 loads
+    // (32 KiB per work-group) in flight.
+    double* sl = reinterpret_cast<double*>(dyn_smem);
+    const int slot = lane >> 4, c = lane & 15;
+    const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
+    double qd[8];
+    {
+      const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        qd[2 * e] = (double)bf16_lo(w[e]);
+        qd[2 * e + 1] = (double)bf16_hi(w[e]);
+      }
+    }
+    const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + c * 8;
+    for (int j0 = 0; j0 < nfull; j0 += 128) {
+      uint4 kr[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * 16 + wave * 4 + slot;
+        kr[u] = make_uint4(0, 0, 0, 0);
+        if (j < nfull) kr[u] = load_stream16(base + (int64_t)j * p.kc_stride_block);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * 16 + wave * 4 + slot;
+        const uint32_t w[4] = {kr[u].x, kr[u].y, kr[u].z, kr[u].w};
+        double acc = 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
+          acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        acc += __shfl_xor(acc, 4);
+        acc += __shfl_xor(acc, 8);
+        if (c == 0 && j < nfull) sl[j] = acc + 0.0;   // -0 -> +0
+      }
+    }
     __syncthreads();
     sc = sl;
   }
@@ -306,9 +353,17 @@ hipError_t launch_gate_score(const GateParams& p, hipStream_t s) {
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
   if (p.nb_max <= kSelectLdsBlocks)
-    hipLaunchKernelGGL(seer_gate_select_kernel<true>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
+    hipLaunchKernelGGL(seer_gate_select_kernel<1>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
   else
-    hipLaunchKernelGGL(seer_gate_select_kernel<false>, grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL(seer_gate_select_kernel<0>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+bool gate_fused_possible(const GateParams& p) { return p.nb_max <= kSelectLdsBlocks; }
+
+hipError_t launch_gate_fused(const GateParams& p, hipStream_t s) {
+  dim3 grid(p.Hkv, p.B);
+  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
   return hipGetLastError();
 }
 

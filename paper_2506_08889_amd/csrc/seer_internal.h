@@ -49,6 +49,8 @@ struct GateParams {
 // Launchers (each returns the hipError_t of the launch).
 hipError_t launch_gate_score(const GateParams& p, hipStream_t s);
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s);
+bool gate_fused_possible(const GateParams& p);
+hipError_t launch_gate_fused(const GateParams& p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_merge(const DecodeParams& p, hipStream_t s);

@@ -114,7 +114,7 @@ def test_argument_errors_are_reported_before_any_launch():
 
 
 def test_knobs_roundtrip():
-    for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0)), (2, (1, 0))):
+    for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0)), (2, (1, 0)), (3, (1, 2, 0))):
         for v in vals:
             seer.set_knob(knob, v)
             assert seer.get_knob(knob) == v

@@ -23,8 +23,8 @@ def sample_groups(G, n, seed):
 
 
 def run_full(name, n_sample, mode=seer.SELECT_TOPK, keep=None, block_size=None):
-    seer.set_knob(0, 0)
-    seer.set_knob(1, 0)
+    for k in (0, 1, 3):
+        seer.set_knob(k, 0)
     w = synth.CONFIGS[name]
     seer.set_knob(2, 1 if (w.seqlen_dist != "fixed" or w.budget_tokens == 0) else 0)   # as bench.py does
     if block_size:

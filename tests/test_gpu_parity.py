@@ -21,18 +21,32 @@ IMPLS = {"valu": 1, "mfma": 2}
 
 @pytest.fixture(autouse=True)
 def _reset_knobs():
-    for k in (0, 1, 2):
+    for k in (0, 1, 2, 3):
         seer.set_knob(k, 0)
     yield
-    for k in (0, 1, 2):
+    for k in (0, 1, 2, 3):
         seer.set_knob(k, 0)
+
+
+def gate_both_impls(*args, **kw):
+    """seer.gate_select through both gate implementations (score + select kernels, fused kernel);
+    the two must agree bit for bit.  Returns the result (the callers compare it with the oracle)."""
+    res = []
+    for impl in (1, 2):
+        seer.set_knob(3, impl)
+        idx, cnt = seer.gate_select(*args, **kw)
+        torch.cuda.synchronize()
+        res.append((idx, cnt))
+    seer.set_knob(3, 0)
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1]), "gate implementations differ"
+    return res[1]
 
 
 def gpu_gate(inp, mode=seer.SELECT_TOPK, threshold=0.0, max_sel=None):
     w = inp.w
-    return seer.gate_select(inp.q_gate, inp.kc, inp.seqlens, w.block_size, mode=mode,
-                            budget_tokens=w.budget_tokens, budget_blocks=inp.budget_blocks,
-                            threshold=threshold, max_sel=max_sel or inp.max_sel)
+    return gate_both_impls(inp.q_gate, inp.kc, inp.seqlens, w.block_size, mode=mode,
+                           budget_tokens=w.budget_tokens, budget_blocks=inp.budget_blocks,
+                           threshold=threshold, max_sel=max_sel or inp.max_sel)
 
 
 def gpu_decode(inp, block_idx, nblk, out_dtype):
@@ -276,18 +290,18 @@ def test_gate_ties_and_edge_rules_bit_exact():
     for budget in (1, bs, 3 * bs + 1, 100 * bs, 299 * bs, 10 ** 6):
         max_sel = min((budget + bs - 1) // bs, nb_max)
         ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_tokens=budget, max_sel=max_sel)
-        gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_tokens=budget, max_sel=max_sel)
+        gi, gc = gate_both_impls(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_tokens=budget, max_sel=max_sel)
         torch.cuda.synchronize()
         check_indices(gi, gc, ri, rc, what=f"ties budget={budget}")
     # per-sequence block budgets, including 0 and more than there are blocks; wider list than needed
     bb = torch.tensor([7, 0, 400, 3, 2, 1], dtype=torch.int32)
     ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_blocks=bb, max_sel=310)
-    gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=310)
+    gi, gc = gate_both_impls(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=310)
     torch.cuda.synchronize()
     check_indices(gi, gc, ri, rc, what="budget_blocks")
     # list narrower than a per-sequence budget: clamped to max_sel
     ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_blocks=bb, max_sel=5)
-    gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=5)
+    gi, gc = gate_both_impls(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, budget_blocks=bb.to(DEV), max_sel=5)
     torch.cuda.synchronize()
     check_indices(gi, gc, ri, rc, what="budget_blocks clamped")
     # threshold: strict comparison on exactly representable probabilities (4 equal scores -> 1/4)
@@ -295,7 +309,7 @@ def test_gate_ties_and_edge_rules_bit_exact():
     sl4 = torch.full((B,), 4 * bs, dtype=torch.int32)
     for tau in (0.25, 0.2499999, 0.0, 1.0):
         ri, rc = oracle.gate_select(qg, kc4, sl4, bs, mode=oracle.SELECT_THRESHOLD, threshold=tau, max_sel=4)
-        gi, gc = seer.gate_select(qg.to(DEV), kc4.to(DEV), sl4.to(DEV), bs, mode=seer.SELECT_THRESHOLD,
+        gi, gc = gate_both_impls(qg.to(DEV), kc4.to(DEV), sl4.to(DEV), bs, mode=seer.SELECT_THRESHOLD,
                                   threshold=tau, max_sel=4)
         torch.cuda.synchronize()
         check_indices(gi, gc, ri, rc, what=f"threshold tau={tau}")
@@ -310,7 +324,7 @@ def test_gate_strided_compression_cache_and_long_context():
     sl = torch.tensor([131072, 131072 - 63], dtype=torch.int32)
     ri, rc = oracle.gate_select(qg, kc, sl, bs, budget_tokens=13107, max_sel=205)
     wd = wide.to(DEV)
-    gi, gc = seer.gate_select(qg.to(DEV), wd[..., 128:], sl.to(DEV), bs, budget_tokens=13107, max_sel=205)
+    gi, gc = gate_both_impls(qg.to(DEV), wd[..., 128:], sl.to(DEV), bs, budget_tokens=13107, max_sel=205)
     torch.cuda.synchronize()
     check_indices(gi, gc, ri, rc, what="strided kc, 2048 blocks")
 
