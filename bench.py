@@ -68,6 +68,7 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware counters)")
     ap.add_argument("--dense-steps", type=int, default=5, help="timed dense flash-decode steps (0 = skip the dense baseline)")
+    ap.add_argument("--also", default="c2", help="second workload reported compactly in the same line ('' = none)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus must be 1. "
@@ -80,11 +81,20 @@ def main():
     import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda:0"
     seer.load_library()
+    result = run_workload(args, args.workload, seer, synth, torch, np, full=True)
+    if args.also and args.also != args.workload:
+        sec = run_workload(args, args.also, seer, synth, torch, np, full=False)
+        result["also"] = {args.also: {k: sec[k] for k in ("value", "unit", "ms_per_step", "config", "roofline",
+                                                           "kernels_avg_us", "dense", "speedup_vs_dense")}}
+    print(json.dumps(result), flush=True)
+
+
+def run_workload(args, workload, seer, synth, torch, np, full):
+    dev = "cuda:0"
     seer.set_knob(0, args.impl)
     seer.set_knob(1, args.splits)
-    w = synth.CONFIGS[args.workload]
+    w = synth.CONFIGS[workload]
     ragged = w.seqlen_dist != "fixed" or w.budget_tokens == 0      # lists of very different lengths
     seer.set_knob(2, 1 if ragged else 0)
     seer.set_knob(3, args.gate_impl)
@@ -247,7 +257,7 @@ def main():
                                       "with_gate": ms_dense / ms_step, "ideal": 1.0 / max(1.0 - sparsity, 1e-9)}
 
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline, also a parity spot check)
-    if not args.no_cpu_baseline:
+    if full and not args.no_cpu_baseline:
         import oracle
         from oracle import KVLayout
         G = B * Hkv
@@ -302,7 +312,9 @@ def main():
             "max_abs_err_out_bf16": float(np.abs(go - oo).max()),
             "max_abs_err_lse": float(np.abs(gl - ol).max())}
 
-    print(json.dumps(result), flush=True)
+    del caches, base
+    torch.cuda.empty_cache()
+    return result
 
 
 if __name__ == "__main__":

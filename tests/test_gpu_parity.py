@@ -340,3 +340,43 @@ def test_results_are_deterministic_run_to_run():
     idx2, cnt2 = gpu_gate(inp)
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2) and torch.equal(cnt, cnt2)
+
+
+def test_hip_graph_capture_and_replay_match_eager():
+    """The two calls allocate nothing, never synchronise and record no memset, so a step can be
+    captured into a HIP graph; every replay must reproduce the eager result bit for bit, with eager
+    work and synchronisations between the replays."""
+    w = synth.scaled(synth.CONFIGS["c2"], B=2, seqlen=4096, budget_tokens=1024)
+    inp = synth.make_inputs(w, DEV)
+    B, Hq, Hkv, d = w.B, w.Hq, w.Hkv, w.d
+    idx = torch.empty(B, Hkv, inp.max_sel, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(B, Hkv, dtype=torch.int32, device=DEV)
+    out = torch.empty(B, Hq, d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(B, Hq, dtype=torch.float32, device=DEV)
+    wsg = torch.empty(seer.gate_workspace_bytes(B, Hkv, inp.nb_max), dtype=torch.uint8, device=DEV)
+    wsd = torch.empty(seer.decode_workspace_bytes(B, Hq, Hkv, d, inp.max_sel), dtype=torch.uint8, device=DEV)
+    seer.set_knob(1, 4)      # several splits: split kernel + merge kernel are both in the graph
+
+    def step():
+        seer.gate_select(inp.q_gate, inp.kc, inp.seqlens, w.block_size, budget_tokens=w.budget_tokens,
+                         max_sel=inp.max_sel, block_idx=idx, nblk=cnt, workspace=wsg)
+        seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, idx, cnt, w.block_size, w.scale, out=out, lse=lse,
+                           workspace=wsd)
+
+    step()
+    torch.cuda.synchronize()
+    ref = (idx.clone(), cnt.clone(), out.clone(), lse.clone())
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in (idx, cnt, out, lse):
+            t.zero_()
+        (inp.q.float() * 2).sum().item()          # unrelated eager work + a synchronisation
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((idx, cnt, out, lse), ref):
+            assert torch.equal(got, want), f"replay {rep} differs from the eager result"
