@@ -69,6 +69,13 @@ def _load():
             ctypes.c_void_p, ctypes.POINTER(_KV), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_gate_q.restype = ctypes.c_int
+        lib.oracle_gate_q.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 5 + \
+            [ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_kc_update.restype = ctypes.c_int
+        lib.oracle_kc_update.argtypes = [ctypes.POINTER(_KV), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -193,3 +200,75 @@ def sparse_decode(q, kv: KVLayout, seqlens, block_idx, nblk, block_size: int, sc
     if rc != 0:
         raise ValueError("oracle_sparse_decode: bad head counts")
     return out, lse
+
+
+def _f32(x) -> np.ndarray:
+    if not isinstance(x, np.ndarray):
+        x = x.cpu().numpy()
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def _kv_struct(k, page_table, page_size, B):
+    kb = _bits(k)
+    es = kb.itemsize
+    assert kb.strides[3] == es
+    st = _KV()
+    st.k = kb.ctypes.data
+    st.v = kb.ctypes.data
+    st.stride_seq, st.stride_head, st.stride_token = (kb.strides[0] // es, kb.strides[1] // es, kb.strides[2] // es)
+    pt = _i32(page_table)
+    if pt is not None:
+        st.page_table, st.max_pages, st.page_size = pt.ctypes.data, pt.shape[1], page_size
+    else:
+        assert kb.shape[0] == B
+        st.page_table, st.max_pages, st.page_size = None, 0, 0
+    return st, kb, pt
+
+
+def gate_q(q_nope, wq, rope_cos, rope_sin, seqlens):
+    """Q branch of the AttnGate (Eq. 1a).  q_nope [B,Hq,d] bf16 (pre-RoPE queries of the current
+    token), wq [Hkv,Dg,g*d] bf16, rope tables [n_pos,Dg/2] fp32, seqlens [B].
+    Returns (q_gate fp64 [B,Hkv,Dg] unrounded, q_gate bf16 bits uint16 [B,Hkv,Dg])."""
+    lib = _load()
+    qb = np.ascontiguousarray(_bits(q_nope))
+    wb = np.ascontiguousarray(_bits(wq))
+    B, Hq, d = qb.shape
+    Hkv, Dg, gd = wb.shape
+    assert Hq % Hkv == 0 and gd == (Hq // Hkv) * d
+    co, si = _f32(rope_cos), _f32(rope_sin)
+    assert co.shape == si.shape and co.shape[1] == Dg // 2
+    sl = _i32(seqlens)
+    out = np.empty((B, Hkv, Dg), dtype=np.float64)
+    bits = np.empty((B, Hkv, Dg), dtype=np.uint16)
+    rc = lib.oracle_gate_q(_ptr(qb), _ptr(wb), _ptr(co), _ptr(si), co.shape[0], _ptr(sl), B, Hq, Hkv, d, Dg,
+                           _ptr(out), _ptr(bits))
+    if rc != 0:
+        raise ValueError(f"oracle_gate_q failed ({rc}): bad head counts or a position beyond the rope table")
+    return out, bits
+
+
+def kc_update(k_nope, wk, rope_cos, rope_sin, seqlens, block_size: int, nb_max: int, *, block_begin=None,
+              block_end=None, page_table=None, page_size: int = 0, out=None, out_bits=None):
+    """K branch of the AttnGate (Eq. 1b): entries [block_begin, block_end) of the K Compression
+    Cache of every sequence (default: all full blocks).  k_nope: pre-RoPE keys in KV-cache layout
+    (contiguous [B,Hkv,S,d] or paged pool), wk [Hkv,Dg,3d] bf16.
+    Returns (kc fp64 [B,Hkv,nb_max,Dg] (NaN where not computed), kc bf16 bits uint16 (0 there))."""
+    lib = _load()
+    wb = np.ascontiguousarray(_bits(wk))
+    Hkv, Dg, d3 = wb.shape
+    d = d3 // 3
+    sl = _i32(seqlens)
+    B = sl.shape[0]
+    st, kb, pt = _kv_struct(k_nope, page_table, page_size, B)
+    assert kb.shape[1] == Hkv and kb.shape[3] == d
+    co, si = _f32(rope_cos), _f32(rope_sin)
+    bb, be = _i32(block_begin), _i32(block_end)
+    if out is None:
+        out = np.full((B, Hkv, nb_max, Dg), np.nan, dtype=np.float64)
+    if out_bits is None:
+        out_bits = np.zeros((B, Hkv, nb_max, Dg), dtype=np.uint16)
+    rc = lib.oracle_kc_update(ctypes.byref(st), _ptr(wb), _ptr(co), _ptr(si), co.shape[0], _ptr(sl), _ptr(bb),
+                              _ptr(be), B, Hkv, d, Dg, nb_max, block_size, _ptr(out), _ptr(out_bits))
+    if rc != 0:
+        raise ValueError(f"oracle_kc_update failed ({rc})")
+    return out, out_bits

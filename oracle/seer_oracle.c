@@ -255,3 +255,139 @@ int oracle_sparse_decode(const uint16_t* q, const oracle_kv_t* kv, const int32_t
   }
   return 0;
 }
+
+/* ------------------------------------------------------- AttnGate front-end (Eq. 1a, 1b) */
+
+/* fp64 -> bf16 bits, round to nearest even (through an exactly representable fp32 when possible;
+ * the double is first rounded to fp32 with the FPU's round-to-nearest-even, then to bf16; to avoid
+ * double rounding the bf16 rounding is done directly on the double's value). */
+static uint16_t f64_to_bf16_bits(double x) {
+  if (x != x) return 0x7fc0;
+  float f = (float)x;                 /* candidate; may suffer double rounding, fixed below */
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  uint32_t lo = u & 0xffff0000u;      /* bf16 neighbours of the fp32 candidate */
+  uint32_t hi = lo + 0x10000u;
+  float flo, fhi;
+  memcpy(&flo, &lo, 4);
+  memcpy(&fhi, &hi, 4);
+  /* flo and fhi bracket x in magnitude (same sign); pick the nearer in exact double arithmetic */
+  double dlo = fabs(x - (double)flo), dhi = fabs((double)fhi - x);
+  if (isinf(fhi) && !isinf(x)) { /* overflow boundary: keep IEEE behaviour of the candidate */ }
+  uint32_t pick;
+  if (dlo < dhi) pick = lo;
+  else if (dhi < dlo) pick = hi;
+  else pick = ((lo >> 16) & 1u) ? hi : lo;   /* tie: even mantissa */
+  return (uint16_t)(pick >> 16);
+}
+
+/* Rotary embedding in the rotate-half convention of the LLaMA/Qwen family: feature c < D/2 is
+ * paired with feature c + D/2; cos_t/sin_t are the caller's tables for this position [D/2]. */
+static void rope_rotate_half(double* y, int D, const float* cos_t, const float* sin_t) {
+  const int half = D / 2;
+  for (int c = 0; c < half; ++c) {
+    const double a = y[c], b = y[c + half];
+    const double co = (double)cos_t[c], si = (double)sin_t[c];
+    y[c] = a * co - b * si;
+    y[c + half] = b * co + a * si;
+  }
+}
+
+/*
+ * Q branch of the AttnGate (Eq. 1a): the g pre-RoPE query heads of a kv head are concatenated
+ * (head-major) into one vector of g*d features, multiplied by that kv head's weight matrix
+ * Wq[h] (Dg x g*d, row-major) and rotated at the position of the current token (seqlens[i] - 1).
+ * q_nope bf16 [B,Hq,d]; wq bf16 [Hkv,Dg,g*d]; rope tables fp32 [n_pos, Dg/2].
+ * out_f64 [B,Hkv,Dg] unrounded, out_bf16 [B,Hkv,Dg] rounded bits (either may be NULL).
+ */
+int oracle_gate_q(const uint16_t* q_nope, const uint16_t* wq, const float* rope_cos, const float* rope_sin,
+                  int n_pos, const int32_t* seqlens, int B, int Hq, int Hkv, int d, int Dg, double* out_f64,
+                  uint16_t* out_bf16) {
+  if (Hkv <= 0 || Hq % Hkv || Dg % 2) return -1;
+  const int g = Hq / Hkv, gd = g * d;
+  int bad = 0;
+#pragma omp parallel for collapse(2)
+  for (int i = 0; i < B; ++i)
+    for (int h = 0; h < Hkv; ++h) {
+      int pos = seqlens[i] - 1;
+      if (pos < 0) pos = 0;
+      if (pos >= n_pos) { bad = 1; pos = n_pos - 1; }
+      const uint16_t* x = q_nope + ((int64_t)i * Hq + (int64_t)h * g) * d;   /* g*d contiguous */
+      double* y = (double*)malloc(sizeof(double) * (size_t)Dg);
+      for (int o = 0; o < Dg; ++o) {
+        const uint16_t* wrow = wq + ((int64_t)h * Dg + o) * gd;
+        double s = 0.0;
+        for (int c = 0; c < gd; ++c) s += bf16_value(wrow[c]) * bf16_value(x[c]);
+        y[o] = s;
+      }
+      rope_rotate_half(y, Dg, rope_cos + (int64_t)pos * (Dg / 2), rope_sin + (int64_t)pos * (Dg / 2));
+      for (int o = 0; o < Dg; ++o) {
+        const int64_t at = ((int64_t)i * Hkv + h) * Dg + o;
+        if (out_f64) out_f64[at] = y[o];
+        if (out_bf16) out_bf16[at] = f64_to_bf16_bits(y[o]);
+      }
+      free(y);
+    }
+  return bad ? -2 : 0;
+}
+
+/*
+ * K branch of the AttnGate (Eq. 1b) = one entry of the K Compression Cache (Sec. 3.2): the b
+ * pre-RoPE keys of block j are max-, min- and average-pooled over the tokens, the three results
+ * concatenated ([max | min | avg], 3d features), multiplied by Wk[h] (Dg x 3d, row-major) and
+ * rotated at the position of the block's first token (j*b).
+ * k_nope uses the KV-cache addressing (kv->k is read; kv->v ignored).  Blocks
+ * [block_begin[i], block_end[i]) of every sequence are computed (clamped to the full blocks of the
+ * sequence, seqlens[i] / b, and to nb_max).  out_f64 / out_bf16: [B,Hkv,nb_max,Dg], entries of
+ * blocks outside the range are left untouched.
+ */
+int oracle_kc_update(const oracle_kv_t* kv, const uint16_t* wk, const float* rope_cos, const float* rope_sin,
+                     int n_pos, const int32_t* seqlens, const int32_t* block_begin, const int32_t* block_end,
+                     int B, int Hkv, int d, int Dg, int nb_max, int block_size, double* out_f64,
+                     uint16_t* out_bf16) {
+  if (Dg % 2) return -1;
+  int bad = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+  for (int i = 0; i < B; ++i)
+    for (int h = 0; h < Hkv; ++h) {
+      int S = seqlens[i];
+      if (S < 0) S = 0;
+      int nfull = S / block_size;
+      if (nfull > nb_max) nfull = nb_max;
+      int j0 = block_begin ? block_begin[i] : 0, j1 = block_end ? block_end[i] : nfull;
+      if (j0 < 0) j0 = 0;
+      if (j1 > nfull) j1 = nfull;
+      double* u = (double*)malloc(sizeof(double) * (size_t)(3 * d));
+      double* y = (double*)malloc(sizeof(double) * (size_t)Dg);
+      for (int j = j0; j < j1; ++j) {
+        for (int c = 0; c < d; ++c) { u[c] = -INFINITY; u[d + c] = INFINITY; u[2 * d + c] = 0.0; }
+        for (int t = 0; t < block_size; ++t) {
+          const uint16_t* row = kv->k + token_offset(kv, i, h, (int64_t)j * block_size + t);
+          for (int c = 0; c < d; ++c) {
+            const double x = bf16_value(row[c]);
+            if (x > u[c]) u[c] = x;
+            if (x < u[d + c]) u[d + c] = x;
+            u[2 * d + c] += x;
+          }
+        }
+        for (int c = 0; c < d; ++c) u[2 * d + c] /= (double)block_size;
+        for (int o = 0; o < Dg; ++o) {
+          const uint16_t* wrow = wk + ((int64_t)h * Dg + o) * (3 * d);
+          double s = 0.0;
+          for (int c = 0; c < 3 * d; ++c) s += bf16_value(wrow[c]) * u[c];
+          y[o] = s;
+        }
+        int64_t pos = (int64_t)j * block_size;
+        if (pos >= n_pos) { bad = 1; pos = n_pos - 1; }
+        rope_rotate_half(y, Dg, rope_cos + pos * (Dg / 2), rope_sin + pos * (Dg / 2));
+        for (int o = 0; o < Dg; ++o) {
+          const int64_t at = (((int64_t)i * Hkv + h) * nb_max + j) * Dg + o;
+          if (out_f64) out_f64[at] = y[o];
+          if (out_bf16) out_bf16[at] = f64_to_bf16_bits(y[o]);
+        }
+      }
+      free(u);
+      free(y);
+    }
+  return bad ? -2 : 0;
+}

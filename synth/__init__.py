@@ -214,3 +214,20 @@ def random_block_lists(B: int, Hkv: int, nb_per_seq, k_per_seq, max_sel: int, ge
             idx[i, h, :k] = sel.to(torch.int32)
             cnt[i, h] = k
     return idx, cnt
+
+
+def rope_tables(n_pos: int, dim: int, base: float = 1.0e6, device="cpu"):
+    """cos/sin tables [n_pos, dim/2] fp32 of the rotary embedding: angle = pos * base^(-2c/dim),
+    evaluated in fp64 and rounded once (base 1e6 as in the Qwen3 family).  These are inputs of the
+    gate front-end calls, like any other tensor."""
+    c = torch.arange(dim // 2, dtype=torch.float64)
+    inv = torch.pow(torch.tensor(base, dtype=torch.float64), -2.0 * c / dim)
+    ang = torch.arange(n_pos, dtype=torch.float64)[:, None] * inv[None, :]
+    return torch.cos(ang).float().to(device), torch.sin(ang).float().to(device)
+
+
+def gate_weights(w: Workload, device, gen: torch.Generator):
+    """Random bf16 gate projections: Wq [Hkv, Dg, g*d] and Wk [Hkv, Dg, 3d], N(0,1)/sqrt(fan-in)."""
+    wq = torch.empty(w.Hkv, w.Dg, w.g * w.d, dtype=torch.float32, device=device).normal_(generator=gen)
+    wk = torch.empty(w.Hkv, w.Dg, 3 * w.d, dtype=torch.float32, device=device).normal_(generator=gen)
+    return ((wq / math.sqrt(w.g * w.d)).to(torch.bfloat16), (wk / math.sqrt(3 * w.d)).to(torch.bfloat16))
