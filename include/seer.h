@@ -156,6 +156,41 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv /* host st
                               float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * AttnGate front-end, Q branch (Eq. 1a): per (sequence i, kv head h) the g pre-RoPE query heads
+ * of the group are concatenated head-major into g*d features, multiplied by that head's weight
+ * matrix wq[h] (Dg x g*d, row-major) and rotated (RoPE, rotate-half pairing: feature c with
+ * c + Dg/2) at the position of the current token, seqlens[i] - 1.  fp32 accumulation, output
+ * rounded to bf16: q_gate is what seer_gate_select consumes.
+ *
+ * q_nope bf16 [B,Hq,d]; wq bf16 [Hkv,Dg,g*d]; rope_cos / rope_sin fp32 [n_pos, Dg/2] (16-byte
+ * aligned; row p holds cos / sin of p * theta_c; positions >= n_pos use the last row);
+ * q_gate out bf16 [B,Hkv,Dg].
+ */
+seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,
+                        int n_pos, const int32_t* seqlens, int B, int Hq, int Hkv, int d, int Dg,
+                        void* q_gate, void* stream);
+
+/*
+ * AttnGate front-end, K branch = K Compression Cache update (Eq. 1b, Sec. 3.2): for every
+ * sequence i, kv head h and block j in [block_begin[i], block_end[i]) (defaults 0 and
+ * seqlens[i]/block_size; always clamped to the full blocks of the sequence and to nb_max): the
+ * block's b pre-RoPE keys are max-, min- and average-pooled over the tokens, concatenated
+ * [max | min | avg] (3d features), multiplied by wk[h] (Dg x 3d, row-major) and rotated at the
+ * position of the block's first token, j*block_size.  The entry is written as bf16 to
+ * kc_cache[i,h,j,:]; other entries are not touched.  Call it for the newest block whenever
+ * seqlens[i] reaches a multiple of block_size (Sec. 3.2), or for all blocks after a prefill.
+ *
+ * k_nope: pre-RoPE keys in KV-cache addressing (k_nope->k is read, ->v ignored).
+ * max_blocks >= the largest block_end[i] - block_begin[i] of the call (it sizes the launch).
+ */
+seer_status seer_kc_update(const seer_kv_layout* k_nope /* host struct */, const void* wk,
+                           const float* rope_cos, const float* rope_sin, int n_pos, const int32_t* seqlens,
+                           const int32_t* block_begin, const int32_t* block_end, int max_blocks, int B,
+                           int Hkv, int d, int Dg, int nb_max, int block_size, void* kc_cache,
+                           int64_t kc_stride_batch, int64_t kc_stride_head, int64_t kc_stride_block,
+                           void* stream);
+
+/*
  * Measurement aid, not part of the method: a plain streaming read of `bytes` bytes (multiple of
  * 16) from device memory `src`, no gather and no arithmetic.  Its rate is the practical HBM read
  * ceiling the decode kernels are compared with.  `sink` is 16 bytes of device memory that the
@@ -194,7 +229,9 @@ typedef enum seer_kernel_class {
   SEER_KERNEL_DECODE_SPLIT = 2,
   SEER_KERNEL_DECODE_MERGE = 3,
   SEER_KERNEL_STREAM_READ = 4,
-  SEER_KERNEL_CLASSES = 5
+  SEER_KERNEL_GATE_Q = 5,
+  SEER_KERNEL_KC_UPDATE = 6,
+  SEER_KERNEL_CLASSES = 7
 } seer_kernel_class;
 seer_status seer_profile_enable(int on);
 seer_status seer_profile_reset(void);

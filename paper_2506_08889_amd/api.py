@@ -20,7 +20,7 @@ KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
 KNOB_DECODE_RAGGED = 2
 KNOB_GATE_IMPL = 3
-KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read")
+KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read", "gate_q", "kc_update")
 
 
 class SeerError(RuntimeError):
@@ -75,6 +75,11 @@ def load_library():
     lib.seer_dense_decode.restype = c_int
     lib.seer_dense_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int,
                                       c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.seer_gate_q.restype = c_int
+    lib.seer_gate_q.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
+    lib.seer_kc_update.restype = c_int
+    lib.seer_kc_update.argtypes = [ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_int, c_int,
+                                   c_int, c_int, c_int, c_int, c_int, c_vp, c_i64, c_i64, c_i64, c_vp]
     lib.seer_hbm_read_probe.restype = c_int
     lib.seer_hbm_read_probe.argtypes = [c_vp, c_sz, c_vp, c_vp]
     lib.seer_set_knob.restype = c_int
@@ -250,6 +255,63 @@ def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: tor
                                workspace.numel(), _stream())
     _check("seer_dense_decode", st)
     return out, lse
+
+
+def _rope(rope_cos, rope_sin, Dg):
+    _want(rope_cos, torch.float32, "rope_cos"); _want(rope_sin, torch.float32, "rope_sin")
+    if rope_cos.shape != rope_sin.shape or rope_cos.dim() != 2 or rope_cos.shape[1] != Dg // 2 or \
+            not (rope_cos.is_contiguous() and rope_sin.is_contiguous()):
+        raise ValueError("rope tables must be contiguous [n_pos, Dg/2] fp32")
+    return rope_cos.shape[0]
+
+
+def gate_q(q_nope: torch.Tensor, wq: torch.Tensor, rope_cos: torch.Tensor, rope_sin: torch.Tensor,
+           seqlens: torch.Tensor, *, q_gate: Optional[torch.Tensor] = None):
+    """seer_gate_q.  q_nope [B,Hq,d] bf16, wq [Hkv,Dg,g*d] bf16, rope tables [n_pos,Dg/2] fp32.
+    Returns q_gate [B,Hkv,Dg] bf16."""
+    lib = load_library()
+    _want(q_nope, torch.bfloat16, "q_nope"); _want(wq, torch.bfloat16, "wq"); _want(seqlens, torch.int32, "seqlens")
+    if not (q_nope.is_contiguous() and wq.is_contiguous()):
+        raise ValueError("q_nope and wq must be contiguous")
+    B, Hq, d = q_nope.shape
+    Hkv, Dg, gd = wq.shape
+    if Hq % Hkv or gd != (Hq // Hkv) * d:
+        raise ValueError("wq must be [Hkv, Dg, (Hq/Hkv)*d]")
+    n_pos = _rope(rope_cos, rope_sin, Dg)
+    if q_gate is None:
+        q_gate = torch.empty(B, Hkv, Dg, dtype=torch.bfloat16, device=q_nope.device)
+    _want(q_gate, torch.bfloat16, "q_gate")
+    st = lib.seer_gate_q(_ptr(q_nope), _ptr(wq), _ptr(rope_cos), _ptr(rope_sin), n_pos, _ptr(seqlens), B, Hq, Hkv,
+                         d, Dg, _ptr(q_gate), _stream())
+    _check("seer_gate_q", st)
+    return q_gate
+
+
+def kc_update(k_nope: torch.Tensor, wk: torch.Tensor, rope_cos: torch.Tensor, rope_sin: torch.Tensor,
+              seqlens: torch.Tensor, block_size: int, kc_cache: torch.Tensor, *, max_blocks: Optional[int] = None,
+              block_begin: Optional[torch.Tensor] = None, block_end: Optional[torch.Tensor] = None,
+              page_table: Optional[torch.Tensor] = None, page_size: int = 0):
+    """seer_kc_update.  k_nope: pre-RoPE keys in KV-cache layout; wk [Hkv,Dg,3d] bf16;
+    kc_cache [B,Hkv,nb_max,Dg] bf16 (updated in place, last dim contiguous)."""
+    lib = load_library()
+    _want(wk, torch.bfloat16, "wk"); _want(seqlens, torch.int32, "seqlens"); _want(kc_cache, torch.bfloat16, "kc_cache")
+    if not wk.is_contiguous() or kc_cache.dim() != 4 or kc_cache.stride(3) != 1:
+        raise ValueError("wk must be contiguous and kc_cache [B,Hkv,nb_max,Dg] contiguous in its last dim")
+    lay = _layout(k_nope, k_nope, page_table, page_size)
+    B, Hkv, nb_max, Dg = kc_cache.shape
+    d = k_nope.shape[3]
+    if wk.shape != (Hkv, Dg, 3 * d):
+        raise ValueError("wk must be [Hkv, Dg, 3*d]")
+    n_pos = _rope(rope_cos, rope_sin, Dg)
+    for name, t in (("block_begin", block_begin), ("block_end", block_end)):
+        if t is not None:
+            _want(t, torch.int32, name)
+    st = lib.seer_kc_update(ctypes.byref(lay), _ptr(wk), _ptr(rope_cos), _ptr(rope_sin), n_pos, _ptr(seqlens),
+                            _ptr(block_begin), _ptr(block_end), max_blocks or nb_max, B, Hkv, d, Dg, nb_max,
+                            block_size, _ptr(kc_cache), kc_cache.stride(0), kc_cache.stride(1), kc_cache.stride(2),
+                            _stream())
+    _check("seer_kc_update", st)
+    return kc_cache
 
 
 def hbm_read_probe(src: torch.Tensor, sink: torch.Tensor):

@@ -300,6 +300,80 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int
                        scale, out, out_dtype, lse, workspace, workspace_bytes, stream);
 }
 
+seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,
+                        int n_pos, const int32_t* seqlens, int B, int Hq, int Hkv, int d, int Dg, void* q_gate,
+                        void* stream) {
+  if (!q_nope || !wq || !rope_cos || !rope_sin || !seqlens || !q_gate) return SEER_ERR_NULL;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || n_pos <= 0 || Hq % Hkv) return SEER_ERR_SHAPE;
+  if (Hkv > 65535) return SEER_ERR_UNSUPPORTED;
+  if (d != seer::kHeadDim || Dg != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup) return SEER_ERR_UNSUPPORTED;
+  if (!aligned16(q_nope) || !aligned16(wq) || !aligned16(rope_cos) || !aligned16(rope_sin) || !aligned16(q_gate))
+    return SEER_ERR_SHAPE;
+  seer::FrontQParams p{};
+  p.q_nope = static_cast<const uint16_t*>(q_nope);
+  p.wq = static_cast<const uint16_t*>(wq);
+  p.rope_cos = rope_cos;
+  p.rope_sin = rope_sin;
+  p.n_pos = n_pos;
+  p.seqlens = seqlens;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.g = Hq / Hkv;
+  p.q_gate = static_cast<uint16_t*>(q_gate);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_GATE_Q, s);
+    e = seer::launch_gate_q(p, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
+seer_status seer_kc_update(const seer_kv_layout* k_nope, const void* wk, const float* rope_cos,
+                           const float* rope_sin, int n_pos, const int32_t* seqlens, const int32_t* block_begin,
+                           const int32_t* block_end, int max_blocks, int B, int Hkv, int d, int Dg, int nb_max,
+                           int block_size, void* kc_cache, int64_t kc_stride_batch, int64_t kc_stride_head,
+                           int64_t kc_stride_block, void* stream) {
+  if (!k_nope || !k_nope->k || !wk || !rope_cos || !rope_sin || !seqlens || !kc_cache) return SEER_ERR_NULL;
+  if (B <= 0 || Hkv <= 0 || n_pos <= 0 || nb_max <= 0 || max_blocks <= 0 || block_size <= 0) return SEER_ERR_SHAPE;
+  if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
+  if (d != seer::kHeadDim || Dg != seer::kHeadDim || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  if (k_nope->stride_token < d || (k_nope->stride_token % 8) || (k_nope->stride_head % 8) || (k_nope->stride_seq % 8))
+    return SEER_ERR_SHAPE;
+  if ((kc_stride_batch % 8) || (kc_stride_head % 8) || (kc_stride_block % 8) || kc_stride_block < Dg)
+    return SEER_ERR_SHAPE;
+  if (!aligned16(k_nope->k) || !aligned16(wk) || !aligned16(rope_cos) || !aligned16(rope_sin) || !aligned16(kc_cache))
+    return SEER_ERR_SHAPE;
+  if (k_nope->page_table &&
+      (k_nope->page_size <= 0 || k_nope->max_pages <= 0 || k_nope->page_size % block_size != 0))
+    return SEER_ERR_SHAPE;
+  seer::FrontKParams p{};
+  p.k_nope = static_cast<const uint16_t*>(k_nope->k);
+  p.stride_seq = k_nope->stride_seq;
+  p.stride_head = k_nope->stride_head;
+  p.stride_token = k_nope->stride_token;
+  p.page_table = k_nope->page_table;
+  p.max_pages = k_nope->max_pages;
+  p.page_size = k_nope->page_size;
+  p.wk = static_cast<const uint16_t*>(wk);
+  p.rope_cos = rope_cos;
+  p.rope_sin = rope_sin;
+  p.n_pos = n_pos;
+  p.seqlens = seqlens;
+  p.block_begin = block_begin;
+  p.block_end = block_end;
+  p.B = B; p.Hkv = Hkv; p.nb_max = nb_max; p.block_size = block_size;
+  p.kc = static_cast<uint16_t*>(kc_cache);
+  p.kc_stride_batch = kc_stride_batch;
+  p.kc_stride_head = kc_stride_head;
+  p.kc_stride_block = kc_stride_block;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_KC_UPDATE, s);
+    e = seer::launch_kc_update(p, max_blocks < nb_max ? max_blocks : nb_max, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
 seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return SEER_ERR_NULL;
   if (bytes < 16 || !aligned16(src) || !aligned16(sink)) return SEER_ERR_SHAPE;

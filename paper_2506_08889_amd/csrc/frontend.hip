@@ -1,0 +1,208 @@
+// AttnGate front-end on gfx950: the Q branch (Eq. 1a) that turns the g pre-RoPE query heads of a
+// kv head into one gate query, and the K branch (Eq. 1b) that turns a block of b pre-RoPE keys
+// into one entry of the K Compression Cache (Sec. 3.2): max / min / average pooling over the
+// tokens, concatenation, a per-kv-head linear layer and RoPE at the block's first position.
+//
+// Both are a batch of matrix-vector products against one weight matrix per kv head, so 16 vectors
+// are processed together as the N side of v_mfma_f32_16x16x32_bf16 (operand layout as in
+// decode_mfma.hip: lane = 16*q + n; A row n, B column n, k = 8q..8q+7; D column n, rows 4q..4q+3).
+// The 128 output features are 8 M-tiles; wave w owns tiles w and w + 4, i.e. features
+// [16w, 16w+16) and their rotate-half partners [64+16w, 64+16w+16), so RoPE is lane-local.
+#include "seer_internal.h"
+
+namespace seer {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ uint32_t pack2_bf16_rne(float a, float b) {
+  return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+}
+
+// Rotate-half RoPE on the two accumulators of a lane (features c = c0..c0+3 and c + 64) and store.
+__device__ __forceinline__ void rope_store(const f32x4_t& lo, const f32x4_t& hi, const float* rope_cos,
+                                           const float* rope_sin, int64_t pos, int c0, uint16_t* dst) {
+  const float4 co = *reinterpret_cast<const float4*>(rope_cos + pos * (kHeadDim / 2) + c0);
+  const float4 si = *reinterpret_cast<const float4*>(rope_sin + pos * (kHeadDim / 2) + c0);
+  const float cv[4] = {co.x, co.y, co.z, co.w}, sv[4] = {si.x, si.y, si.z, si.w};
+  float zl[4], zh[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    zl[r] = lo[r] * cv[r] - hi[r] * sv[r];
+    zh[r] = hi[r] * cv[r] + lo[r] * sv[r];
+  }
+  *reinterpret_cast<uint2*>(dst + c0) = make_uint2(pack2_bf16_rne(zl[0], zl[1]), pack2_bf16_rne(zl[2], zl[3]));
+  *reinterpret_cast<uint2*>(dst + kHeadDim / 2 + c0) =
+      make_uint2(pack2_bf16_rne(zh[0], zh[1]), pack2_bf16_rne(zh[2], zh[3]));
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Q branch.  Grid (ceil(B/16), Hkv); a work-group handles 16 sequences of one kv head.
+// B operand straight from q_nope (the g heads of a group are contiguous: g*128 features).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void seer_gate_q_kernel(FrontQParams p) {
+  const int h = blockIdx.y, i0 = blockIdx.x * 16;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n16 = lane & 15, q4 = lane >> 4;
+  const int gd = p.g * kHeadDim;
+  const int i = i0 + n16;
+  const bool valid = i < p.B;
+
+  const uint16_t* x = p.q_nope + ((int64_t)(valid ? i : 0) * p.Hq + (int64_t)h * p.g) * kHeadDim + q4 * 8;
+  const uint16_t* w0 = p.wq + ((int64_t)h * kHeadDim + 16 * wave + n16) * gd + q4 * 8;
+  const uint16_t* w1 = w0 + (int64_t)64 * gd;
+  f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  for (int kk = 0; kk < gd / 32; ++kk) {
+    uint4 b = make_uint4(0, 0, 0, 0);
+    if (valid) b = *reinterpret_cast<const uint4*>(x + kk * 32);
+    const uint4 a0 = *reinterpret_cast<const uint4*>(w0 + kk * 32);
+    const uint4 a1 = *reinterpret_cast<const uint4*>(w1 + kk * 32);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0), __builtin_bit_cast(bf16x8_t, b), acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1), __builtin_bit_cast(bf16x8_t, b), acc1, 0, 0, 0);
+  }
+  if (!valid) return;
+  int64_t pos = (int64_t)p.seqlens[i] - 1;
+  pos = pos < 0 ? 0 : (pos >= p.n_pos ? p.n_pos - 1 : pos);
+  rope_store(acc0, acc1, p.rope_cos, p.rope_sin, pos, 16 * wave + 4 * q4,
+             p.q_gate + ((int64_t)i * p.Hkv + h) * kHeadDim);
+}
+
+// ---------------------------------------------------------------------------------------------
+// K branch.  Grid (ceil(max_blocks/16), Hkv, B); a work-group handles 16 consecutive blocks of one
+// (sequence, kv head): each wave pools 4 of them (16 lanes per 256-byte key row, coalesced,
+// non-temporal), the pooled vectors go to a swizzled LDS tile as the B operand
+// [max | min | avg_hi | avg_lo] (the fp32 average is carried as two bf16 terms so the bf16 MFMA
+// loses nothing; the weight columns of the average are simply used twice), then
+// Y[128 x 16] = W U^T, RoPE, store.  Memory-bound on the key read: 256 B per (token, kv head).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void seer_kc_update_kernel(FrontKParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char u_lds[16 * 1024];   // 16 blocks x 512 bf16
+
+  const int h = blockIdx.y, i = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n16 = lane & 15, q4 = lane >> 4;
+  const int bs = p.block_size;
+
+  int S = p.seqlens[i];
+  S = S < 0 ? 0 : S;
+  int nfull = S / bs;
+  nfull = nfull < p.nb_max ? nfull : p.nb_max;
+  int j0 = p.block_begin ? p.block_begin[i] : 0;
+  int j1 = p.block_end ? p.block_end[i] : nfull;
+  j0 = j0 < 0 ? 0 : j0;
+  j1 = j1 > nfull ? nfull : j1;
+  const int jt = j0 + blockIdx.x * 16;          // first block of this tile
+  if (jt >= j1) return;
+
+  // ---- pooling: wave w handles blocks jt + 4w .. jt + 4w + 3 --------------------------------
+  for (int bb = 0; bb < 4; ++bb) {
+    const int n = 4 * wave + bb;
+    const int j = jt + n;
+    float mx[8], mn[8], sm[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
+    if (j < j1) {
+      const int64_t t0 = (int64_t)j * bs;
+      int64_t off;
+      if (p.page_table) {
+        int64_t pi = t0 / p.page_size;
+        pi = pi >= p.max_pages ? p.max_pages - 1 : pi;
+        off = (int64_t)p.page_table[(int64_t)i * p.max_pages + pi] * p.stride_seq + (int64_t)h * p.stride_head +
+              (t0 % p.page_size) * p.stride_token;
+      } else {
+        off = (int64_t)i * p.stride_seq + (int64_t)h * p.stride_head + t0 * p.stride_token;
+      }
+      const uint16_t* base = p.k_nope + off + n16 * 8;
+      for (int t = q4; t < bs; t += 32) {          // 8 rows of this lane per trip
+        uint4 r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          r[u] = make_uint4(0, 0, 0, 0);
+          if (t + 4 * u < bs) r[u] = load_stream16(base + (int64_t)(t + 4 * u) * p.stride_token);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (t + 4 * u < bs) {
+            const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
+              mx[2 * e] = fmaxf(mx[2 * e], a); mx[2 * e + 1] = fmaxf(mx[2 * e + 1], b);
+              mn[2 * e] = fminf(mn[2 * e], a); mn[2 * e + 1] = fminf(mn[2 * e + 1], b);
+              sm[2 * e] += a; sm[2 * e + 1] += b;
+            }
+          }
+        }
+      }
+    }
+    // combine the 4 row groups of the wave
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
+      mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
+      sm[e] += __shfl_xor(sm[e], 16); sm[e] += __shfl_xor(sm[e], 32);
+    }
+    if (q4 == 0) {
+      uint32_t pmx[4], pmn[4], phi[4], plo[4];
+      const float inv = 1.0f / (float)bs;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a0 = mx[2 * e], a1 = mx[2 * e + 1], b0 = mn[2 * e], b1 = mn[2 * e + 1];
+        if (j >= j1) { a0 = a1 = b0 = b1 = 0.f; }
+        pmx[e] = (__float_as_uint(a0) >> 16) | (__float_as_uint(a1) & 0xffff0000u);   // exact bf16 values
+        pmn[e] = (__float_as_uint(b0) >> 16) | (__float_as_uint(b1) & 0xffff0000u);
+        const float v0 = sm[2 * e] * inv, v1 = sm[2 * e + 1] * inv;
+        const uint16_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
+        const float r0 = v0 - __uint_as_float((uint32_t)h0 << 16), r1 = v1 - __uint_as_float((uint32_t)h1 << 16);
+        phi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        plo[e] = pack2_bf16_rne(r0, r1);
+      }
+      // U[n][part*128 + 8*n16 .. +8]: 16-byte chunk index part*16 + n16, swizzled with n
+      unsigned char* row = u_lds + n * 1024;
+      *reinterpret_cast<uint4*>(row + (((0 * 16 + n16) ^ n) << 4)) = make_uint4(pmx[0], pmx[1], pmx[2], pmx[3]);
+      *reinterpret_cast<uint4*>(row + (((1 * 16 + n16) ^ n) << 4)) = make_uint4(pmn[0], pmn[1], pmn[2], pmn[3]);
+      *reinterpret_cast<uint4*>(row + (((2 * 16 + n16) ^ n) << 4)) = make_uint4(phi[0], phi[1], phi[2], phi[3]);
+      *reinterpret_cast<uint4*>(row + (((3 * 16 + n16) ^ n) << 4)) = make_uint4(plo[0], plo[1], plo[2], plo[3]);
+    }
+  }
+  __syncthreads();
+
+  // ---- Y = W U^T for this wave's two M-tiles --------------------------------------------------
+  const int d3 = 3 * kHeadDim;
+  const uint16_t* w0 = p.wk + ((int64_t)h * kHeadDim + 16 * wave + n16) * d3 + q4 * 8;
+  const uint16_t* w1 = w0 + (int64_t)64 * d3;
+  f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int kk = 0; kk < 16; ++kk) {
+    const int wcol = (kk < 12 ? kk : kk - 4) * 32;          // avg_lo reuses the average's weight columns
+    const uint4 a0 = *reinterpret_cast<const uint4*>(w0 + wcol);
+    const uint4 a1 = *reinterpret_cast<const uint4*>(w1 + wcol);
+    const uint4 b = *reinterpret_cast<const uint4*>(u_lds + n16 * 1024 + (((kk * 4 + q4) ^ n16) << 4));
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0), __builtin_bit_cast(bf16x8_t, b), acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1), __builtin_bit_cast(bf16x8_t, b), acc1, 0, 0, 0);
+  }
+  const int j = jt + n16;
+  if (j >= j1) return;
+  int64_t pos = (int64_t)j * bs;
+  pos = pos >= p.n_pos ? p.n_pos - 1 : pos;
+  rope_store(acc0, acc1, p.rope_cos, p.rope_sin, pos, 16 * wave + 4 * q4,
+             p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + (int64_t)j * p.kc_stride_block);
+}
+
+hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s) {
+  dim3 grid((p.B + 15) / 16, p.Hkv);
+  hipLaunchKernelGGL(seer_gate_q_kernel, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, hipStream_t s) {
+  dim3 grid((max_blocks + 15) / 16, p.Hkv, p.B);
+  hipLaunchKernelGGL(seer_kc_update_kernel, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace seer

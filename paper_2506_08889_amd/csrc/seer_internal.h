@@ -46,7 +46,37 @@ struct GateParams {
   double* scores;               // workspace [B,Hkv,nb_max]
 };
 
+struct FrontQParams {
+  const uint16_t* q_nope;       // bf16 [B,Hq,128] pre-RoPE queries of the current token
+  const uint16_t* wq;           // bf16 [Hkv,128,g*128]
+  const float* rope_cos;        // [n_pos,64]
+  const float* rope_sin;
+  int32_t n_pos;
+  const int32_t* seqlens;
+  int32_t B, Hq, Hkv, g;
+  uint16_t* q_gate;             // bf16 [B,Hkv,128]
+};
+
+struct FrontKParams {
+  const uint16_t* k_nope;       // pre-RoPE keys, KV-cache addressing
+  int64_t stride_seq, stride_head, stride_token;
+  const int32_t* page_table;
+  int32_t max_pages, page_size;
+  const uint16_t* wk;           // bf16 [Hkv,128,384]
+  const float* rope_cos;
+  const float* rope_sin;
+  int32_t n_pos;
+  const int32_t* seqlens;
+  const int32_t* block_begin;   // [B] or nullptr
+  const int32_t* block_end;     // [B] or nullptr
+  int32_t B, Hkv, nb_max, block_size;
+  uint16_t* kc;
+  int64_t kc_stride_batch, kc_stride_head, kc_stride_block;
+};
+
 // Launchers (each returns the hipError_t of the launch).
+hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s);
+hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, hipStream_t s);
 hipError_t launch_gate_score(const GateParams& p, hipStream_t s);
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s);
 bool gate_fused_possible(const GateParams& p);

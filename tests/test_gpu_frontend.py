@@ -1,0 +1,106 @@
+"""GPU parity of the AttnGate front-end (Eq. 1a / 1b) against the fp64 oracle, and the whole chain
+front-end -> selection -> sparse decode.  The front-end outputs are bf16: the GPU value must lie
+within one bf16 rounding step of the oracle's unrounded fp64 value (fp32 accumulation error is far
+below that), and must equal the oracle's rounded value almost everywhere."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2506_08889_amd as seer
+import synth
+from helpers import check_decode, check_indices, cpu
+from oracle import KVLayout
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bf16_close(got_bf16, ref_f64, ref_bits, what, min_exact=0.98):
+    g = got_bf16.float().cpu().numpy().astype(np.float64)
+    sel = ~np.isnan(ref_f64)
+    err = np.abs(g[sel] - ref_f64[sel])
+    tol = np.abs(ref_f64[sel]) * 2.0 ** -8 + 1e-5          # half a bf16 step is 2^-9 relative; allow a full one
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} values off by more than a bf16 step (max err {err.max():.3e})"
+    gb = got_bf16.cpu().view(torch.int16).numpy().view(np.uint16)
+    exact = (gb[sel] == ref_bits[sel]).mean()
+    assert exact >= min_exact, f"{what}: only {exact:.4f} of the values equal the correctly rounded result"
+    return exact
+
+
+@pytest.mark.parametrize("g,B", [(4, 37), (5, 16), (1, 3), (8, 2)])
+def test_gate_q_matches_oracle(g, B):
+    Hkv = 8
+    w = synth.Workload("fq", B=B, Hq=g * Hkv, Hkv=Hkv, seqlen=5000)
+    gen = synth.generator(DEV, 100 + g)
+    q_nope = synth.randn_bf16((B, w.Hq, w.d), DEV, gen)
+    wq, _ = synth.gate_weights(w, DEV, gen)
+    cos, sin = synth.rope_tables(6000, w.Dg, device=DEV)
+    sl = torch.randint(1, 6000, (B,), generator=torch.Generator().manual_seed(g), dtype=torch.int32)
+    got = seer.gate_q(q_nope, wq, cos, sin, sl.to(DEV))
+    torch.cuda.synchronize()
+    ref, bits = oracle.gate_q(q_nope.cpu(), wq.cpu(), cos.cpu(), sin.cpu(), sl)
+    bf16_close(got, ref, bits, f"gate_q g={g}")
+
+
+@pytest.mark.parametrize("bs,paged", [(64, False), (128, False), (64, True), (32, False), (16, False)])
+def test_kc_update_matches_oracle(bs, paged):
+    w = synth.Workload("fk", B=3, Hq=8, Hkv=2, block_size=bs, seqlen_range=(bs * 3, bs * 41 + 17),
+                       seqlen_dist="uniform", paged=paged, budget_tokens=bs, seed=bs + paged)
+    inp = synth.make_inputs(w, DEV)              # inp.k plays the role of the pre-RoPE key cache
+    gen = synth.generator(DEV, 200 + bs)
+    _, wk = synth.gate_weights(w, DEV, gen)
+    n_pos = inp.nb_max * bs + 1
+    cos, sin = synth.rope_tables(n_pos, w.Dg, device=DEV)
+    kc = torch.full((w.B, w.Hkv, inp.nb_max, w.Dg), 7.0, dtype=torch.bfloat16, device=DEV)
+    seer.kc_update(inp.k, wk, cos, sin, inp.seqlens, bs, kc, page_table=inp.page_table, page_size=inp.page_size)
+    torch.cuda.synchronize()
+    ref, bits = oracle.kc_update(cpu(inp.k), wk.cpu(), cos.cpu(), sin.cpu(), inp.seqlens_cpu, bs, inp.nb_max,
+                                 page_table=cpu(inp.page_table), page_size=inp.page_size)
+    bf16_close(kc, ref, bits, f"kc_update bs={bs} paged={paged}")
+    # entries of partial / absent blocks were not touched
+    untouched = np.isnan(ref)
+    assert (kc.float().cpu().numpy()[untouched] == 7.0).all()
+    # incremental update of a block range reproduces the same entries and touches nothing else
+    kc2 = torch.full_like(kc, 7.0)
+    nfull = (inp.seqlens_cpu // bs)
+    begin = (nfull - 1).clamp(min=0).to(torch.int32)
+    seer.kc_update(inp.k, wk, cos, sin, inp.seqlens, bs, kc2, max_blocks=1, block_begin=begin.to(DEV),
+                   block_end=nfull.to(torch.int32).to(DEV), page_table=inp.page_table, page_size=inp.page_size)
+    torch.cuda.synchronize()
+    for i in range(w.B):
+        j = int(nfull[i]) - 1
+        assert torch.equal(kc2[i, :, j], kc[i, :, j])
+        assert (kc2[i, :, :j] == 7.0).all() and (kc2[i, :, j + 1:] == 7.0).all()
+
+
+def test_front_end_to_decode_chain():
+    """Raw pre-RoPE Q/K -> gate inputs -> block selection -> sparse decode, every stage against the
+    oracle on the inputs the GPU stage actually received."""
+    w = synth.scaled(synth.CONFIGS["c2"], B=3, seqlen=64 * 70 + 9, budget_tokens=64 * 12)
+    inp = synth.make_inputs(w, DEV)
+    gen = synth.generator(DEV, 300)
+    q_nope = synth.randn_bf16((w.B, w.Hq, w.d), DEV, gen)
+    k_nope = synth.randn_bf16(tuple(inp.k.shape), DEV, gen)
+    wq, wk = synth.gate_weights(w, DEV, gen)
+    cos, sin = synth.rope_tables(inp.nb_max * 64 + 1, w.Dg, device=DEV)
+    q_gate = seer.gate_q(q_nope, wq, cos, sin, inp.seqlens)
+    kc = torch.zeros(w.B, w.Hkv, inp.nb_max, w.Dg, dtype=torch.bfloat16, device=DEV)
+    seer.kc_update(k_nope, wk, cos, sin, inp.seqlens, 64, kc)
+    idx, cnt = seer.gate_select(q_gate, kc, inp.seqlens, 64, budget_tokens=w.budget_tokens, max_sel=inp.max_sel)
+    out, lse = seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, idx, cnt, 64, w.scale, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    rq, rq_bits = oracle.gate_q(q_nope.cpu(), wq.cpu(), cos.cpu(), sin.cpu(), inp.seqlens_cpu)
+    bf16_close(q_gate, rq, rq_bits, "chain q_gate")
+    rk, rk_bits = oracle.kc_update(k_nope.cpu(), wk.cpu(), cos.cpu(), sin.cpu(), inp.seqlens_cpu, 64, inp.nb_max)
+    bf16_close(kc, rk, rk_bits, "chain kc")
+    ri, rc = oracle.gate_select(q_gate.cpu(), kc.cpu(), inp.seqlens_cpu, 64, budget_tokens=w.budget_tokens,
+                                max_sel=inp.max_sel)
+    check_indices(idx, cnt, ri, rc, what="chain selection")
+    ro, rl = oracle.sparse_decode(inp.q.cpu(), KVLayout(inp.k.cpu(), inp.v.cpu()), inp.seqlens_cpu, ri, rc, 64, w.scale)
+    check_decode(out, lse, ro, rl, tight=True, what="chain decode")
+    # the partial last block (9 tokens) is selected although it has no cache entry
+    assert (idx.cpu()[:, :, :].max(dim=2).values == 70).all()
