@@ -195,6 +195,57 @@ def run_workload(args, workload, seer, synth, torch, np, full):
     stream_gbps = probe_bytes / (tot_p / n_p * 1e-3) / 1e9
     seer.profile_reset()
 
+    # ---- AttnGate front-end (reported beside the step, not part of `value`): the per-step query
+    # branch, the K Compression Cache rebuilt for every block (as after a prefill; the K tensor stands in
+    # for the pre-RoPE keys) and the one-block update a sequence needs when it completes a block.
+    frontend = None
+    if full:
+        gen2 = synth.generator(dev, w.seed + 2000)
+        wq, wk = synth.gate_weights(w, dev, gen2)
+        n_pos = base.nb_max * bs + 1
+        rcos, rsin = synth.rope_tables(n_pos, w.Dg, device=dev)
+        kc_out = torch.empty_like(base.kc)
+        qg_out = torch.empty_like(base.q_gate)
+        nfull_cpu = (base.seqlens_cpu // bs).to(torch.int32)
+        last_begin = (nfull_cpu - 1).clamp(min=0).to(dev)
+        last_end = nfull_cpu.to(dev)
+
+        def fe_q(i):
+            seer.gate_q(qs[i % R], wq, rcos, rsin, base.seqlens, q_gate=qg_out)
+
+        def fe_full(i):
+            seer.kc_update(caches[0][0], wk, rcos, rsin, base.seqlens, bs, kc_out, page_table=base.page_table,
+                           page_size=base.page_size)
+
+        def fe_last(i):
+            seer.kc_update(caches[0][0], wk, rcos, rsin, base.seqlens, bs, kc_out, max_blocks=1,
+                           block_begin=last_begin, block_end=last_end, page_table=base.page_table,
+                           page_size=base.page_size)
+
+        for fn in (fe_q, fe_full, fe_last):
+            fn(0)
+        seer.profile_reset()
+        seer.profile_enable(True)
+        ms_q = timed(fe_q, 20)
+        nq, tq = seer.profile_read(5)
+        seer.profile_reset()
+        ms_full = timed(fe_full, 3)
+        nf, tf = seer.profile_read(6)
+        seer.profile_reset()
+        ms_last = timed(fe_last, 20)
+        nl, tl = seer.profile_read(6)
+        seer.profile_enable(False)
+        seer.profile_reset()
+        kc_bytes = int(nfull_cpu.to(torch.int64).sum()) * Hkv * (bs * w.d * 2 + w.Dg * 2)
+        full_us = tf / nf * 1e3
+        frontend = {"gate_q_us": tq / nq * 1e3, "gate_q_ms_per_call": ms_q,
+                    "kc_update_all_blocks": {"kernel_us": full_us, "algorithmic_bytes": kc_bytes,
+                                             "GBps": kc_bytes / (full_us * 1e-6) / 1e9,
+                                             "frac_hbm_peak": kc_bytes / (full_us * 1e-6) / 1e9 / HBM_PEAK_GBPS},
+                    "kc_update_last_block_us": tl / nl * 1e3,
+                    "ms_per_step_with_gate_q": ms_step + ms_q}
+        del wq, wk, rcos, rsin, kc_out
+
     if args.calibrate_copy_mib > 0:
         a = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         b_ = torch.empty_like(a)
@@ -245,6 +296,7 @@ def run_workload(args, workload, seer, synth, torch, np, full):
         "ms_per_step_with_events": ms_step_prof,
         "gate_GBps": ab["gate"] / (((kern["gate_score"]["avg_us"] or 0.0) + (kern["gate_select"]["avg_us"] or 0.0)) * 1e-6) / 1e9,
         "stream_read_GBps": stream_gbps,
+        "frontend": frontend,
         "dense": None, "speedup_vs_dense": None,
         "paper_context": "paper: up to 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware, not a target)",
     }

@@ -369,7 +369,7 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope, const void* wk, const f
   hipError_t e;
   {
     Timed t(SEER_KERNEL_KC_UPDATE, s);
-    e = seer::launch_kc_update(p, max_blocks < nb_max ? max_blocks : nb_max, s);
+    e = seer::launch_kc_update(p, max_blocks < nb_max ? max_blocks : nb_max, cu_count(), s);
   }
   return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
 }

@@ -56,13 +56,20 @@ __global__ __launch_bounds__(256) void seer_gate_q_kernel(FrontQParams p) {
   const uint16_t* w0 = p.wq + ((int64_t)h * kHeadDim + 16 * wave + n16) * gd + q4 * 8;
   const uint16_t* w1 = w0 + (int64_t)64 * gd;
   f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-  for (int kk = 0; kk < gd / 32; ++kk) {
-    uint4 b = make_uint4(0, 0, 0, 0);
-    if (valid) b = *reinterpret_cast<const uint4*>(x + kk * 32);
-    const uint4 a0 = *reinterpret_cast<const uint4*>(w0 + kk * 32);
-    const uint4 a1 = *reinterpret_cast<const uint4*>(w1 + kk * 32);
-    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0), __builtin_bit_cast(bf16x8_t, b), acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1), __builtin_bit_cast(bf16x8_t, b), acc1, 0, 0, 0);
+  for (int kk0 = 0; kk0 < gd / 32; kk0 += 4) {     // gd / 32 = 4 g: always a multiple of 4
+    uint4 b[4], a0[4], a1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      b[u] = make_uint4(0, 0, 0, 0);
+      if (valid) b[u] = *reinterpret_cast<const uint4*>(x + (kk0 + u) * 32);
+      a0[u] = *reinterpret_cast<const uint4*>(w0 + (kk0 + u) * 32);
+      a1[u] = *reinterpret_cast<const uint4*>(w1 + (kk0 + u) * 32);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0[u]), __builtin_bit_cast(bf16x8_t, b[u]), acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1[u]), __builtin_bit_cast(bf16x8_t, b[u]), acc1, 0, 0, 0);
+    }
   }
   if (!valid) return;
   int64_t pos = (int64_t)p.seqlens[i] - 1;
@@ -79,7 +86,7 @@ __global__ __launch_bounds__(256) void seer_gate_q_kernel(FrontQParams p) {
 // loses nothing; the weight columns of the average are simply used twice), then
 // Y[128 x 16] = W U^T, RoPE, store.  Memory-bound on the key read: 256 B per (token, kv head).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void seer_kc_update_kernel(FrontKParams p) {
+__global__ __launch_bounds__(256, 2) void seer_kc_update_kernel(FrontKParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char u_lds[16 * 1024];   // 16 blocks x 512 bf16
 
   const int h = blockIdx.y, i = blockIdx.z;
@@ -95,102 +102,139 @@ __global__ __launch_bounds__(256) void seer_kc_update_kernel(FrontKParams p) {
   int j1 = p.block_end ? p.block_end[i] : nfull;
   j0 = j0 < 0 ? 0 : j0;
   j1 = j1 > nfull ? nfull : j1;
-  const int jt = j0 + blockIdx.x * 16;          // first block of this tile
-  if (jt >= j1) return;
+  if (j0 + (int)blockIdx.x * p.tiles_per_wg * 16 >= j1) return;
+
+  // The weight rows of this wave (2 M-tiles x 512 input features) stay in registers for all tiles
+  // of the work-group: re-reading them per tile cost as many (poorly coalesced) load instructions
+  // as the keys themselves.
+  const int d3 = 3 * kHeadDim;
+  uint4 wa0[16], wa1[16];
+  {
+    const uint16_t* w0 = p.wk + ((int64_t)h * kHeadDim + 16 * wave + n16) * d3 + q4 * 8;
+    const uint16_t* w1 = w0 + (int64_t)64 * d3;
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      const int wcol = (kk < 12 ? kk : kk - 4) * 32;        // avg_lo reuses the average's weight columns
+      wa0[kk] = *reinterpret_cast<const uint4*>(w0 + wcol);
+      wa1[kk] = *reinterpret_cast<const uint4*>(w1 + wcol);
+    }
+  }
+
+  for (int tile = 0; tile < p.tiles_per_wg; ++tile) {
+  const int jt = j0 + ((int)blockIdx.x * p.tiles_per_wg + tile) * 16;   // first block of this tile
+  if (jt >= j1) break;
+  if (tile > 0) __syncthreads();                 // the previous tile's pooled vectors have been consumed
 
   // ---- pooling: wave w handles blocks jt + 4w .. jt + 4w + 3 --------------------------------
-  for (int bb = 0; bb < 4; ++bb) {
+  // The rows of a lane (q4, q4 + 4, ...) are taken 8 at a time ("chunk"); the loads of the next
+  // chunk - possibly of the next block - are issued before the current chunk is reduced.
+  const int trips = (bs + 31) >> 5;              // chunks per block
+  const int nchunks = 4 * trips;
+  auto block_base = [&](int j) -> const uint16_t* {
+    const int64_t t0 = (int64_t)j * bs;
+    int64_t off;
+    if (p.page_table) {
+      int64_t pi = t0 / p.page_size;
+      pi = pi >= p.max_pages ? p.max_pages - 1 : pi;
+      off = (int64_t)p.page_table[(int64_t)i * p.max_pages + pi] * p.stride_seq + (int64_t)h * p.stride_head +
+            (t0 % p.page_size) * p.stride_token;
+    } else {
+      off = (int64_t)i * p.stride_seq + (int64_t)h * p.stride_head + t0 * p.stride_token;
+    }
+    return p.k_nope + off + n16 * 8;
+  };
+  auto load_chunk = [&](uint4 (&r)[8], int ch) {
+    const int bb = ch / trips, trip = ch - bb * trips;
+    const int j = jt + 4 * wave + bb;
+    const int t = q4 + 32 * trip;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r[u] = make_uint4(0, 0, 0, 0);
+    if (j < j1) {
+      const uint16_t* base = block_base(j);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (t + 4 * u < bs) r[u] = load_stream16(base + (int64_t)(t + 4 * u) * p.stride_token);
+    }
+  };
+
+  float mx[8], mn[8], sm[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
+  uint4 cur[8], nxt[8];
+  load_chunk(cur, 0);
+  for (int ch = 0; ch < nchunks; ++ch) {
+    if (ch + 1 < nchunks) load_chunk(nxt, ch + 1);
+    const int bb = ch / trips, trip = ch - bb * trips;
     const int n = 4 * wave + bb;
     const int j = jt + n;
-    float mx[8], mn[8], sm[8];
+    const int t = q4 + 32 * trip;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
-    if (j < j1) {
-      const int64_t t0 = (int64_t)j * bs;
-      int64_t off;
-      if (p.page_table) {
-        int64_t pi = t0 / p.page_size;
-        pi = pi >= p.max_pages ? p.max_pages - 1 : pi;
-        off = (int64_t)p.page_table[(int64_t)i * p.max_pages + pi] * p.stride_seq + (int64_t)h * p.stride_head +
-              (t0 % p.page_size) * p.stride_token;
-      } else {
-        off = (int64_t)i * p.stride_seq + (int64_t)h * p.stride_head + t0 * p.stride_token;
-      }
-      const uint16_t* base = p.k_nope + off + n16 * 8;
-      for (int t = q4; t < bs; t += 32) {          // 8 rows of this lane per trip
-        uint4 r[8];
+    for (int u = 0; u < 8; ++u) {
+      if (t + 4 * u < bs) {
+        const uint32_t w[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          r[u] = make_uint4(0, 0, 0, 0);
-          if (t + 4 * u < bs) r[u] = load_stream16(base + (int64_t)(t + 4 * u) * p.stride_token);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          if (t + 4 * u < bs) {
-            const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
-              mx[2 * e] = fmaxf(mx[2 * e], a); mx[2 * e + 1] = fmaxf(mx[2 * e + 1], b);
-              mn[2 * e] = fminf(mn[2 * e], a); mn[2 * e + 1] = fminf(mn[2 * e + 1], b);
-              sm[2 * e] += a; sm[2 * e + 1] += b;
-            }
-          }
+        for (int e = 0; e < 4; ++e) {
+          const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
+          mx[2 * e] = fmaxf(mx[2 * e], a); mx[2 * e + 1] = fmaxf(mx[2 * e + 1], b);
+          mn[2 * e] = fminf(mn[2 * e], a); mn[2 * e + 1] = fminf(mn[2 * e + 1], b);
+          sm[2 * e] += a; sm[2 * e + 1] += b;
         }
       }
     }
-    // combine the 4 row groups of the wave
+    if (trip == trips - 1) {
+      // block complete: combine the 4 row groups of the wave, write its pooled vector, reset
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
-      mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
-      sm[e] += __shfl_xor(sm[e], 16); sm[e] += __shfl_xor(sm[e], 32);
-    }
-    if (q4 == 0) {
-      uint32_t pmx[4], pmn[4], phi[4], plo[4];
-      const float inv = 1.0f / (float)bs;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float a0 = mx[2 * e], a1 = mx[2 * e + 1], b0 = mn[2 * e], b1 = mn[2 * e + 1];
-        if (j >= j1) { a0 = a1 = b0 = b1 = 0.f; }
-        pmx[e] = (__float_as_uint(a0) >> 16) | (__float_as_uint(a1) & 0xffff0000u);   // exact bf16 values
-        pmn[e] = (__float_as_uint(b0) >> 16) | (__float_as_uint(b1) & 0xffff0000u);
-        const float v0 = sm[2 * e] * inv, v1 = sm[2 * e + 1] * inv;
-        const uint16_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
-        const float r0 = v0 - __uint_as_float((uint32_t)h0 << 16), r1 = v1 - __uint_as_float((uint32_t)h1 << 16);
-        phi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        plo[e] = pack2_bf16_rne(r0, r1);
+      for (int e = 0; e < 8; ++e) {
+        mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
+        mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
+        sm[e] += __shfl_xor(sm[e], 16); sm[e] += __shfl_xor(sm[e], 32);
       }
-      // U[n][part*128 + 8*n16 .. +8]: 16-byte chunk index part*16 + n16, swizzled with n
-      unsigned char* row = u_lds + n * 1024;
-      *reinterpret_cast<uint4*>(row + (((0 * 16 + n16) ^ n) << 4)) = make_uint4(pmx[0], pmx[1], pmx[2], pmx[3]);
-      *reinterpret_cast<uint4*>(row + (((1 * 16 + n16) ^ n) << 4)) = make_uint4(pmn[0], pmn[1], pmn[2], pmn[3]);
-      *reinterpret_cast<uint4*>(row + (((2 * 16 + n16) ^ n) << 4)) = make_uint4(phi[0], phi[1], phi[2], phi[3]);
-      *reinterpret_cast<uint4*>(row + (((3 * 16 + n16) ^ n) << 4)) = make_uint4(plo[0], plo[1], plo[2], plo[3]);
+      if (q4 == 0) {
+        uint32_t pmx[4], pmn[4], phi[4], plo[4];
+        const float inv = 1.0f / (float)bs;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float a0 = mx[2 * e], a1 = mx[2 * e + 1], b0 = mn[2 * e], b1 = mn[2 * e + 1];
+          if (j >= j1) { a0 = a1 = b0 = b1 = 0.f; }
+          pmx[e] = (__float_as_uint(a0) >> 16) | (__float_as_uint(a1) & 0xffff0000u);   // exact bf16 values
+          pmn[e] = (__float_as_uint(b0) >> 16) | (__float_as_uint(b1) & 0xffff0000u);
+          const float v0 = sm[2 * e] * inv, v1 = sm[2 * e + 1] * inv;
+          const uint16_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
+          const float r0 = v0 - __uint_as_float((uint32_t)h0 << 16), r1 = v1 - __uint_as_float((uint32_t)h1 << 16);
+          phi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          plo[e] = pack2_bf16_rne(r0, r1);
+        }
+        // U[n][part*128 + 8*n16 .. +8]: 16-byte chunk index part*16 + n16, swizzled with n
+        unsigned char* row = u_lds + n * 1024;
+        *reinterpret_cast<uint4*>(row + (((0 * 16 + n16) ^ n) << 4)) = make_uint4(pmx[0], pmx[1], pmx[2], pmx[3]);
+        *reinterpret_cast<uint4*>(row + (((1 * 16 + n16) ^ n) << 4)) = make_uint4(pmn[0], pmn[1], pmn[2], pmn[3]);
+        *reinterpret_cast<uint4*>(row + (((2 * 16 + n16) ^ n) << 4)) = make_uint4(phi[0], phi[1], phi[2], phi[3]);
+        *reinterpret_cast<uint4*>(row + (((3 * 16 + n16) ^ n) << 4)) = make_uint4(plo[0], plo[1], plo[2], plo[3]);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
     }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
   }
   __syncthreads();
 
   // ---- Y = W U^T for this wave's two M-tiles --------------------------------------------------
-  const int d3 = 3 * kHeadDim;
-  const uint16_t* w0 = p.wk + ((int64_t)h * kHeadDim + 16 * wave + n16) * d3 + q4 * 8;
-  const uint16_t* w1 = w0 + (int64_t)64 * d3;
   f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+#pragma unroll
   for (int kk = 0; kk < 16; ++kk) {
-    const int wcol = (kk < 12 ? kk : kk - 4) * 32;          // avg_lo reuses the average's weight columns
-    const uint4 a0 = *reinterpret_cast<const uint4*>(w0 + wcol);
-    const uint4 a1 = *reinterpret_cast<const uint4*>(w1 + wcol);
     const uint4 b = *reinterpret_cast<const uint4*>(u_lds + n16 * 1024 + (((kk * 4 + q4) ^ n16) << 4));
-    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0), __builtin_bit_cast(bf16x8_t, b), acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1), __builtin_bit_cast(bf16x8_t, b), acc1, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa0[kk]), __builtin_bit_cast(bf16x8_t, b), acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa1[kk]), __builtin_bit_cast(bf16x8_t, b), acc1, 0, 0, 0);
   }
   const int j = jt + n16;
-  if (j >= j1) return;
-  int64_t pos = (int64_t)j * bs;
-  pos = pos >= p.n_pos ? p.n_pos - 1 : pos;
-  rope_store(acc0, acc1, p.rope_cos, p.rope_sin, pos, 16 * wave + 4 * q4,
-             p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + (int64_t)j * p.kc_stride_block);
+  if (j < j1) {
+    int64_t pos = (int64_t)j * bs;
+    pos = pos >= p.n_pos ? p.n_pos - 1 : pos;
+    rope_store(acc0, acc1, p.rope_cos, p.rope_sin, pos, 16 * wave + 4 * q4,
+               p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + (int64_t)j * p.kc_stride_block);
+  }
+  }   // tile loop
 }
 
 hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s) {
@@ -199,8 +243,14 @@ hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, hipStream_t s) {
-  dim3 grid((max_blocks + 15) / 16, p.Hkv, p.B);
+hipError_t launch_kc_update(const FrontKParams& p0, int max_blocks, int cus, hipStream_t s) {
+  FrontKParams p = p0;
+  const long tiles = (max_blocks + 15) / 16;
+  // enough work-groups for ~8 per CU, at most 16 tiles (256 blocks) per work-group
+  long per = tiles * p.Hkv * p.B / ((long)cus * 8);
+  per = per < 1 ? 1 : (per > 16 ? 16 : per);
+  p.tiles_per_wg = (int)per;
+  dim3 grid((unsigned)((tiles + per - 1) / per), p.Hkv, p.B);
   hipLaunchKernelGGL(seer_kc_update_kernel, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }

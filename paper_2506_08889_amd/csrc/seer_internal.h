@@ -70,13 +70,14 @@ struct FrontKParams {
   const int32_t* block_begin;   // [B] or nullptr
   const int32_t* block_end;     // [B] or nullptr
   int32_t B, Hkv, nb_max, block_size;
+  int32_t tiles_per_wg;         // 16-block tiles handled by one work-group (set by the launcher)
   uint16_t* kc;
   int64_t kc_stride_batch, kc_stride_head, kc_stride_block;
 };
 
 // Launchers (each returns the hipError_t of the launch).
 hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s);
-hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, hipStream_t s);
+hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, int cus, hipStream_t s);
 hipError_t launch_gate_score(const GateParams& p, hipStream_t s);
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s);
 bool gate_fused_possible(const GateParams& p);
