@@ -53,7 +53,8 @@ typedef enum seer_status {
 
 typedef enum seer_select_mode {
   SEER_SELECT_TOPK = 0,      /* token budget -> block budget -> top-k (Sec. 3.1)    */
-  SEER_SELECT_THRESHOLD = 1  /* softmaxed gate score > threshold (Sec. 3.1)         */
+  SEER_SELECT_THRESHOLD = 1, /* softmaxed gate score > threshold (Sec. 3.1)         */
+  SEER_SELECT_TOPP = 2       /* smallest set of best blocks with gate mass >= p (Sec. 6.2) */
 } seer_select_mode;
 
 typedef enum seer_dtype { SEER_BF16 = 0, SEER_F32 = 1 } seer_dtype;
@@ -108,13 +109,19 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
  *              equal scores resolved towards the lower block index.  k = 0 selects nothing.
  *   THRESHOLD: S_j = softmax_j(s_j / sqrt(Dg)) over the full blocks, in fp64; blocks with
  *              S_j > threshold (strict) are selected, plus the last block if it is partial.
+ *   TOPP:      nucleus selection, the adaptive-sparsity direction named in Sec. 6.2: walking the
+ *              full blocks from the highest score down (equal scores: lower index first), blocks
+ *              are kept until their accumulated S_j reaches p (passed in `threshold`); at least one
+ *              block is kept; p beyond the total mass keeps all; plus the partial last block.
+ *              (Masses are summed in 2^-62 fixed point, so a prefix whose mass lies within ~1e-15
+ *              of p may be cut one block earlier or later than a sequential fp64 sum would.)
  * Output: block_idx[i,h,0..n) ascending block ids, block_idx[i,h,n..max_sel) = -1, nblk[i,h] = n.
  *
  * q_gate   bf16 [B,Hkv,Dg] contiguous.
  * kc_cache bf16, element (i,h,j,c) at i*kc_stride_batch + h*kc_stride_head + j*kc_stride_block + c.
  * seqlens  int32 [B]: tokens in the cache including the current one.
  * budget_blocks int32 [B] or NULL.  threshold is only read in THRESHOLD mode.
- * Errors: THRESHOLD mode needs max_sel >= nb_max (SEER_ERR_CAPACITY); TOPK mode with a token
+ * Errors: THRESHOLD and TOPP modes need max_sel >= nb_max (SEER_ERR_CAPACITY); TOPK mode with a token
  * budget needs max_sel >= min(ceil(budget_tokens/block_size), nb_max) (SEER_ERR_CAPACITY).
  */
 seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t kc_stride_batch,

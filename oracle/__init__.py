@@ -25,6 +25,7 @@ _lib = None
 
 SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
+SELECT_TOPP = 2
 
 
 def build(force: bool = False) -> str:

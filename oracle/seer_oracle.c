@@ -86,6 +86,7 @@ static int by_int(const void* a, const void* b) {
  *         clamped to [0, min(nb, max_sel)].  With a partial last block, that block takes
  *         one of the k slots and the other k-1 go to the best full blocks.
  * mode 1: threshold on the softmax over full blocks; the partial last block is added.
+ * mode 2: top-p on the same softmax (threshold carries p); the partial last block is added.
  * Output per group: ascending block indices, padded with -1 to max_sel; count in nblk.
  * scores_out (optional, [B,Hkv,nb_max]) receives the raw scores (NaN where not computed).
  * Returns 0, or -1 when a threshold selection does not fit max_sel.
@@ -135,7 +136,7 @@ int oracle_gate_select(const uint16_t* q_gate, const uint16_t* kc_cache, int64_t
         for (int r = 0; r < from_full; ++r) sel[n++] = order[r].j;
         if (partial && k > 0) sel[n++] = nb - 1;
         free(order);
-      } else {
+      } else if (mode == 1) {
         if (nfull > 0) {
           const double inv = 1.0 / sqrt((double)Dg);
           double m = -INFINITY;
@@ -146,6 +147,28 @@ int oracle_gate_select(const uint16_t* q_gate, const uint16_t* kc_cache, int64_t
             double Sj = exp(scores[j] * inv - m) / Z;
             if (Sj > threshold) sel[n++] = j;
           }
+        }
+        if (partial) sel[n++] = nb - 1;
+      } else {
+        /* top-p (nucleus) selection, named as the way to adaptive sparsity in Sec. 6.2: walk the
+         * blocks from the highest score down (equal scores: lower index first) and keep them until
+         * their accumulated gate probability reaches p; at least one block is kept. */
+        if (nfull > 0) {
+          const double inv = 1.0 / sqrt((double)Dg);
+          double m = -INFINITY;
+          for (int j = 0; j < nfull; ++j) { double x = scores[j] * inv; if (x > m) m = x; }
+          double Z = 0.0;
+          for (int j = 0; j < nfull; ++j) Z += exp(scores[j] * inv - m);
+          scored_t* order = (scored_t*)malloc(sizeof(scored_t) * (size_t)nfull);
+          for (int j = 0; j < nfull; ++j) { order[j].s = scores[j]; order[j].j = j; }
+          qsort(order, (size_t)nfull, sizeof(scored_t), by_score_then_index);
+          double cum = 0.0;
+          for (int r = 0; r < nfull; ++r) {
+            sel[n++] = order[r].j;
+            cum += exp(order[r].s * inv - m) / Z;
+            if (cum >= threshold) break;
+          }
+          free(order);
         }
         if (partial) sel[n++] = nb - 1;
       }

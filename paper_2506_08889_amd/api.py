@@ -16,6 +16,7 @@ _lib = None
 
 SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
+SELECT_TOPP = 2
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
 KNOB_DECODE_RAGGED = 2

@@ -221,11 +221,11 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
   if (B <= 0 || Hkv <= 0 || Dg <= 0 || nb_max <= 0 || block_size <= 0 || max_sel <= 0) return SEER_ERR_SHAPE;
   if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
   if (Dg != seer::kHeadDim || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
-  if (mode != SEER_SELECT_TOPK && mode != SEER_SELECT_THRESHOLD) return SEER_ERR_UNSUPPORTED;
+  if (mode != SEER_SELECT_TOPK && mode != SEER_SELECT_THRESHOLD && mode != SEER_SELECT_TOPP) return SEER_ERR_UNSUPPORTED;
   if ((kc_stride_batch % 8) || (kc_stride_head % 8) || (kc_stride_block % 8) || kc_stride_block < Dg)
     return SEER_ERR_SHAPE;
   if (!aligned16(q_gate) || !aligned16(kc_cache)) return SEER_ERR_SHAPE;
-  if (mode == SEER_SELECT_THRESHOLD) {
+  if (mode == SEER_SELECT_THRESHOLD || mode == SEER_SELECT_TOPP) {
     if (!(threshold == threshold)) return SEER_ERR_SHAPE;   // NaN
     if (max_sel < nb_max) return SEER_ERR_CAPACITY;
   } else if (!budget_blocks) {

@@ -142,6 +142,8 @@ template <int SRC>
 __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
   __shared__ int hist[256];
+  __shared__ unsigned long long mass[256];   // top-p: fixed-point probability mass per digit
+  __shared__ unsigned long long mass_sel[2];
   __shared__ int wcnt[8];
   __shared__ int digit_sel[3];
   __shared__ double red[4];
@@ -291,6 +293,85 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
       for (int j = tid; j < nfull; j += 256) z += exp(__dsub_rn(__dmul_rn(sc[j], p.inv_sqrt_dg), m));
       Z = wg_reduce_sum(z, red);
     }
+    if (p.mode == 2 && nfull > 0) {
+      // Top-p: the same radix walk as top-k, but steered by probability mass instead of counts.
+      // Masses are accumulated as 2^-62 fixed point, so the sums are exact integers and do not
+      // depend on the order in which the work-group adds them.
+      const double kFix = 4611686018427387904.0;   // 2^62
+      auto fixed_mass = [&](double s) -> unsigned long long {
+        const double Sj = __ddiv_rn(exp(__dsub_rn(__dmul_rn(s, p.inv_sqrt_dg), m)), Z);
+        return (unsigned long long)(Sj * kFix);
+      };
+      unsigned long long want = p.threshold >= 1.0 ? (unsigned long long)kFix
+                                : (p.threshold > 0.0 ? (unsigned long long)(p.threshold * kFix) : 0ull);
+      if (want == 0) want = 1;                       // at least the best block
+      uint64_t prefix = 0, kmask = 0;
+      bool done = false;
+      for (int pass = 7; pass >= 0 && !done; --pass) {
+        const int shift = pass * 8;
+        hist[tid] = 0;
+        mass[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < nfull; j += 256) {
+          const double s = sc[j];
+          const uint64_t key = score_key(s);
+          if ((key & kmask) == prefix) {
+            const int dgt = (int)((key >> shift) & 0xff);
+            atomicAdd(&hist[dgt], 1);
+            atomicAdd(&mass[dgt], fixed_mass(s));
+          }
+        }
+        __syncthreads();
+        if (wave == 0) {
+          const int d0 = 255 - 4 * lane;
+          const unsigned long long m0 = mass[d0], m1 = mass[d0 - 1], m2 = mass[d0 - 2], m3 = mass[d0 - 3];
+          const unsigned long long own = m0 + m1 + m2 + m3;
+          unsigned long long incl = own;
+#pragma unroll
+          for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long x = __shfl_up(incl, o);
+            if (lane >= o) incl += x;
+          }
+          unsigned long long above = incl - own;
+          if (lane == 63 && incl < want) {           // p exceeds the mass that is there: keep everything
+            digit_sel[0] = -1;
+          }
+          if (above < want && want <= incl) {
+            int dsel = d0;
+            unsigned long long bm = m0;
+            if (want > above + m0) {
+              above += m0; dsel = d0 - 1; bm = m1;
+              if (want > above + m1) {
+                above += m1; dsel = d0 - 2; bm = m2;
+                if (want > above + m2) { above += m2; dsel = d0 - 3; bm = m3; }
+              }
+            }
+            digit_sel[0] = dsel;
+            digit_sel[2] = hist[dsel];
+            mass_sel[0] = want - above;              // mass still needed from that bin
+            mass_sel[1] = bm;
+          }
+        }
+        __syncthreads();
+        const int dsel = digit_sel[0];
+        if (dsel < 0) {                              // keep every full block
+          T = 0; take_ge = true; done = true;
+        } else {
+          prefix |= (uint64_t)dsel << shift;
+          kmask |= 0xffull << shift;
+          want = mass_sel[0];
+          if (digit_sel[2] == 1) { T = prefix; take_ge = true; done = true; }   // that block completes the nucleus
+          else if (pass == 0) {
+            // several blocks with exactly this score: equal masses, take as many as are needed
+            const unsigned long long each = mass_sel[1] / (unsigned long long)digit_sel[2];
+            long long c = each ? (long long)((want + each - 1) / each) : digit_sel[2];
+            c = c < 1 ? 1 : (c > digit_sel[2] ? digit_sel[2] : c);
+            T = prefix; need_eq = (int)c; done = true;
+          }
+        }
+        __syncthreads();
+      }
+    }
   }
 
   // ---- ordered compaction: thread t owns block ids [t*run, (t+1)*run) -----------------------
@@ -302,7 +383,7 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     const int j1 = (j0 + run < nfull) ? j0 + run : nfull;
     auto classify = [&](int j, bool* gt, bool* eq) {
       const double s = sc[j];
-      if (p.mode == 0) {
+      if (p.mode != 1) {
         const uint64_t key = score_key(s);
         *gt = take_ge ? key >= T : key > T;
         *eq = !take_ge && key == T;

@@ -142,3 +142,29 @@ def gather_groups(t, w, groups, per_head):
     groups = np.asarray(groups)
     bi, hi = groups // w.Hkv, groups % w.Hkv
     return torch.stack([t[int(b), int(h) * per_head:(int(h) + 1) * per_head] for b, h in zip(bi, hi)])
+
+
+def pick_top_p(scores, seqlens, block_size, dg, lo, hi, tries=64, seed=0):
+    """A nucleus mass p in [lo, hi] that keeps every group's accumulated probability curve as far
+    as possible from p at the cut (so the order of summation cannot move a cut)."""
+    curves = []
+    B, Hkv, _ = scores.shape
+    for i in range(B):
+        nfull = int(seqlens[i]) // block_size
+        for h in range(Hkv):
+            if nfull == 0:
+                continue
+            s = scores[i, h, :nfull]
+            x = s / math.sqrt(dg)
+            e = np.exp(x - x.max())
+            P = e / e.sum()
+            order = np.lexsort((np.arange(nfull), -s))
+            curves.append(np.cumsum(P[order]))
+    rng = np.random.default_rng(seed)
+    best, best_margin = None, -1.0
+    for p in rng.uniform(lo, hi, size=tries):
+        margin = min(np.abs(c - p).min() for c in curves)
+        if margin > best_margin:
+            best, best_margin = float(p), margin
+    assert best_margin > 1e-10, best_margin
+    return best

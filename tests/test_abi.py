@@ -102,7 +102,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert gate(qg=None) == -1
     assert gate(nk=None) == -1
     assert gate(Dg=64) == -3
-    assert gate(mode=2) == -3
+    assert gate(mode=3) == -3
+    assert gate(mode=2, max_sel=16) == -5              # top-p may select every block too
     assert gate(bs=100) == -3
     assert gate(budget=-5) == -2
     assert gate(sj=64) == -2

@@ -12,7 +12,7 @@ import torch
 import oracle
 import paper_2506_08889_amd as seer
 import synth
-from helpers import check_decode, check_indices, cpu, oracle_decode, oracle_gate, pick_threshold
+from helpers import check_decode, check_indices, cpu, oracle_decode, oracle_gate, pick_threshold, pick_top_p
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -380,3 +380,82 @@ def test_hip_graph_capture_and_replay_match_eager():
         torch.cuda.synchronize()
         for got, want in zip((idx, cnt, out, lse), ref):
             assert torch.equal(got, want), f"replay {rep} differs from the eager result"
+
+
+@pytest.mark.parametrize("impl", ["valu", "mfma"])
+@pytest.mark.parametrize("ns", [1, 3, 5])
+def test_needles_at_slice_and_block_boundaries(impl, ns):
+    """A key aligned with one query head (logit far above the rest) placed, in turn, at the first
+    token of the first listed block, the first and last token of the first and last block of every
+    slice of the list, the last valid token of the partial block, and in an unselected block (must
+    change nothing).  Catches gather-addressing, tail-masking and slice-boundary mistakes that the
+    1e-2 tolerance would hide on plain random data."""
+    seer.set_knob(0, IMPLS[impl])
+    seer.set_knob(1, ns)
+    bs, nsel = 64, 23
+    base = small_inputs(90 + ns, B=1, Hq=8, Hkv=2, S=(64 * 40 + 21,))
+    gen = torch.Generator().manual_seed(7)
+    idx, cnt = synth.random_block_lists(1, 2, [41], [nsel], nsel, gen, ascending=False)
+    idx[0, 0, 11] = 40                                    # the partial block (21 tokens) inside the list
+    idx[0, 1] = idx[0, 0]
+    listed = idx[0, 0].tolist()
+    assert len(set(listed)) == nsel
+    unselected = next(j for j in range(40) if j not in listed)
+    L = -(-nsel // ns)
+    spots = [(listed[0], 0)]
+    for s in range(0, nsel, L):
+        first, last = listed[s], listed[min(s + L, nsel) - 1]
+        for blk in (first, last):
+            ntok = 21 if blk == 40 else bs
+            spots += [(blk, 0), (blk, ntok - 1)]
+    spots += [(40, 20), (unselected, 5)]
+    dev_idx, dev_cnt = idx.to(DEV), cnt.to(DEV)
+    for blk, tok in dict.fromkeys(spots):
+        inp = small_inputs(90 + ns, B=1, Hq=8, Hkv=2, S=(64 * 40 + 21,))
+        pos = blk * bs + tok
+        inp.k[0, 0, pos] = (inp.q[0, 2].float() * 5.0).to(torch.bfloat16)     # head 2 -> kv head 0
+        inp.k[0, 1, pos] = (inp.q[0, 5].float() * 5.0).to(torch.bfloat16)     # head 5 -> kv head 1
+        inp = to_dev(inp)
+        ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+        out, lse = gpu_decode(inp, dev_idx, dev_cnt, torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"needle at block {blk} token {tok} ({impl}, ns={ns})")
+        if blk != unselected:      # the needle really dominates its head
+            v_row = inp.v[0, 0, pos].float().cpu().numpy()
+            assert np.abs(ref_out[0, 2] - v_row).max() < 0.05
+
+
+@pytest.mark.parametrize("bs", [64, 128])
+def test_top_p_selection_and_decode(bs):
+    """Nucleus (top-p) block selection, bit-exact against the oracle, then decode on the ragged lists."""
+    w = synth.scaled(synth.CONFIGS["c5"], B=6, block_size=bs, seqlen_range=(300, 9000), name=f"topp_b{bs}")
+    inp = synth.make_inputs(w, DEV)
+    _, _, scores = oracle_gate(inp, return_scores=True)
+    seer.set_knob(2, 1)
+    for lo, hi in ((0.2, 0.4), (0.5, 0.7), (0.85, 0.97)):
+        p = pick_top_p(scores, inp.seqlens_cpu, bs, w.Dg, lo, hi)
+        ref_idx, ref_cnt = oracle_gate(inp, mode=oracle.SELECT_TOPP, threshold=p, max_sel=inp.nb_max)
+        print(f"[top-p] {w.name} p={p:.6f} selected={int(ref_cnt.sum())}", flush=True)
+        gi, gc = gpu_gate(inp, mode=seer.SELECT_TOPP, threshold=p, max_sel=inp.nb_max)
+        check_indices(gi, gc, ref_idx, ref_cnt, what=f"{w.name} top-p {p:.4f}")
+        ref_out, ref_lse = oracle_decode(inp, ref_idx, ref_cnt)
+        out, lse = gpu_decode(inp, gi, gc, torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"{w.name} top-p {p:.4f}")
+    # edge values of p and exact ties
+    for p in (0.0, 1.0, 7.0, -1.0):
+        ref_idx, ref_cnt = oracle_gate(inp, mode=oracle.SELECT_TOPP, threshold=p, max_sel=inp.nb_max)
+        gi, gc = gpu_gate(inp, mode=seer.SELECT_TOPP, threshold=p, max_sel=inp.nb_max)
+        if p == 1.0:        # whether the rounded masses reach exactly 1 is not defined: all but a few tail blocks
+            assert (gc.cpu().numpy() <= ref_cnt + 0).all() or (gc.cpu().numpy() >= ref_cnt - 3).all()
+            continue
+        check_indices(gi, gc, ref_idx, ref_cnt, what=f"top-p edge p={p}")
+    gen = torch.Generator().manual_seed(3)
+    qg = torch.randint(-2, 3, (2, 2, 128), generator=gen).to(torch.bfloat16)
+    kc = torch.randint(-1, 2, (2, 2, 40, 128), generator=gen).to(torch.bfloat16)
+    kc[1] = kc[1, 0, 0]                                   # 40 equal scores: probability 1/40 each
+    sl = torch.tensor([40 * bs, 40 * bs], dtype=torch.int32)
+    for p in (0.26, 0.5001, 0.999):
+        ri, rc = oracle.gate_select(qg, kc, sl, bs, mode=oracle.SELECT_TOPP, threshold=p, max_sel=40)
+        gi, gc = gate_both_impls(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, mode=seer.SELECT_TOPP, threshold=p, max_sel=40)
+        check_indices(gi[1:], gc[1:], ri[1:], rc[1:], what=f"top-p ties p={p}")

@@ -158,17 +158,9 @@ def test_k_branch_block_ranges_and_paged_layout():
 
 
 def test_rounding_to_bf16_is_nearest_even_without_double_rounding():
-    # exact ties and near-ties around 1.0 (bf16 has 7 explicit mantissa bits: spacing 2^-7 at 1.0)
-    vals = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -40, 1.0 + 2.0 ** -8 - 2.0 ** -40,
-            -(1.0 + 2.0 ** -8), 0.0, -0.0, 3.0e-39, 1.0e38, 1.0 + 2.0 ** -8 + 2.0 ** -30]
-    want = [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, 1.0, -1.0, 0.0, -0.0, None, None, 1.0 + 2.0 ** -7]
-    # feed them through the Q branch: one query feature = 1, weight row o holds... instead use a direct path:
-    # Wq = I on head 0, q = value is impossible (q is bf16), so check through the K branch mean:
-    # block of 2^k tokens whose mean is the wanted double is awkward too - use ctypes on the C function directly.
-    import ctypes
-    lib = oracle._load()
-    # the rounding helper is static; exercise it through oracle_gate_q with d = Dg = 2, g = 1, pos 0:
-    # y_0 = w00*x0 + w01*x1 lets us build 1 + 2^-8 exactly (1*1 + 2^-8*1) from bf16 operands.
+    # bf16 has 7 explicit mantissa bits (spacing 2^-7 at 1.0).  The rounding helper is internal to the
+    # oracle, so it is exercised through the Q branch with d = Dg = 2, g = 1 at position 0:
+    # y_0 = sum_c w[0][c] * x[c] builds values such as 1 + 2^-8 exactly from bf16-representable terms.
     def through_q(terms):
         """terms: list of (w, x) bf16-representable pairs; returns (fp64 sum, bf16 bits) of feature 0."""
         n = len(terms)
@@ -179,8 +171,6 @@ def test_rounding_to_bf16_is_nearest_even_without_double_rounding():
         cos = torch.ones(1, 1); sin = torch.zeros(1, 1)
         out, bits = oracle.gate_q(q, w, cos, sin, torch.tensor([1], dtype=torch.int32))
         return out[0, 0, 0], bits[0, 0, 0]
-    def bf(x):
-        return torch.tensor([x], dtype=torch.float64).float().to(torch.bfloat16)   # only used on exactly representable x
     cases = [
         ([(1.0, 1.0), (2.0 ** -8, 1.0)], 1.0),                       # tie -> even (1.0)
         ([(1.0, 1.0), (2.0 ** -8, 1.0), (2.0 ** -7, 1.0)], 1.0 + 2.0 ** -6),   # 1 + 3*2^-8: tie -> even (1 + 2^-6)

@@ -443,3 +443,38 @@ def test_bf16_inputs_are_read_exactly_including_subnormal_and_negative_zero():
     _, _, s = oracle.gate_select(qg, kc, torch.tensor([8 * 64], dtype=torch.int32), 64, budget_tokens=64,
                                  max_sel=8, return_scores=True)
     np.testing.assert_array_equal(s[0, 0], t.float().numpy().astype(np.float64))
+
+
+def test_top_p_mode_matches_sorted_cumulative_probabilities():
+    """Nucleus selection (the adaptive-sparsity direction of Sec. 6.2): smallest prefix of the
+    score-descending order whose softmax mass reaches p."""
+    qg, kc = gate_case(16, B=2, Hkv=2, nb_max=50)
+    b = 64
+    sl = torch.tensor([50 * b, 41 * b + 3], dtype=torch.int32)
+    qf, kf = f64(qg), f64(kc)
+    prev = None
+    for p in (0.0, 0.05, 0.3, 0.5, 0.9, 0.999, 1.0, 1.5):
+        idx, cnt = oracle.gate_select(qg, kc, sl, b, mode=oracle.SELECT_TOPP, threshold=p, max_sel=50)
+        for i, (nfull, partial) in enumerate(((50, False), (41, True))):
+            for h in range(2):
+                s = kf[i, h, :nfull] @ qf[i, h]
+                P = softmax(s / math.sqrt(128))
+                order = np.lexsort((np.arange(nfull), -s))            # score descending, index ascending
+                cum = np.cumsum(P[order])
+                k = int(np.searchsorted(cum, p, side="left")) + 1      # first prefix with cum >= p
+                k = min(max(k, 1), nfull)
+                # keep away from razor edges where summation order could matter
+                assert p <= 0 or p > 1 or k == nfull or min(abs(cum[k - 1] - p), abs(cum[k - 2] - p) if k > 1 else 1) > 1e-9
+                want = sorted(order[:k].tolist()) + ([41] if partial else [])
+                assert idx[i, h, :cnt[i, h]].tolist() == want, (p, i, h)
+        if prev is not None:
+            assert (cnt >= prev).all()           # the nucleus grows with p
+        prev = cnt.copy()
+    assert prev.tolist() == [[50, 50], [42, 42]]  # p beyond the total mass keeps every block
+    idx, cnt = oracle.gate_select(qg, kc, sl, b, mode=oracle.SELECT_TOPP, threshold=0.0, max_sel=50)
+    assert cnt.tolist() == [[1, 1], [2, 2]]       # at least the best block (plus the forced partial one)
+    # equal scores: probability 1/8 each, p = 0.5 needs exactly 4, the lowest indices
+    kc8 = kc[:, :, :8].clone(); kc8[:] = kc[0, 0, 0]
+    idx, cnt = oracle.gate_select(qg, kc8, torch.tensor([8 * b, 8 * b], dtype=torch.int32), b, mode=oracle.SELECT_TOPP,
+                                  threshold=0.5, max_sel=8)
+    assert (cnt == 4).all() and idx[0, 0, :4].tolist() == [0, 1, 2, 3]
