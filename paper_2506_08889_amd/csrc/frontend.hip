@@ -14,6 +14,8 @@ namespace seer {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x2_t __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -157,65 +159,94 @@ __global__ __launch_bounds__(256, 2) void seer_kc_update_kernel(FrontKParams p) 
     }
   };
 
-  float mx[8], mn[8], sm[8];
+  // Running statistics of the current block, per lane 8 features (4 words of 2 bf16):
+  //   max / min on the raw 16-bit patterns made order-preserving (magnitude bits flipped for
+  //   negative values) with packed int16 max / min - no unpacking, no NaN canonicalisation;
+  //   sum by v_dot2_f32_bf16 against (1, 1) on row pairs interleaved with one byte permute.
+  uint32_t smax[4], smin[4];
+  float sm[8];
+  auto reset_stats = [&]() {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
-  uint4 cur[8], nxt[8];
-  load_chunk(cur, 0);
-  for (int ch = 0; ch < nchunks; ++ch) {
-    if (ch + 1 < nchunks) load_chunk(nxt, ch + 1);
+    for (int e = 0; e < 4; ++e) { smax[e] = 0x80008000u; smin[e] = 0x7fff7fffu; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm[e] = 0.f;
+  };
+  auto sortable = [](uint32_t w) -> uint32_t {       // involution: also maps back
+    const s16x2_t v = __builtin_bit_cast(s16x2_t, w);
+    return __builtin_bit_cast(uint32_t, (s16x2_t)(v ^ ((v >> 15) & (short)0x7fff)));
+  };
+  const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+  auto reduce_rows = [&](const uint4 (&r)[8], int nrow) {     // nrow = 4 or 8 valid rows (uniform)
+#pragma unroll
+    for (int u = 0; u < 8; u += 2) {
+      if (u < nrow) {
+        const uint32_t a[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+        const uint32_t b[4] = {r[u + 1].x, r[u + 1].y, r[u + 1].z, r[u + 1].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const s16x2_t ta = __builtin_bit_cast(s16x2_t, sortable(a[e])), tb = __builtin_bit_cast(s16x2_t, sortable(b[e]));
+          const s16x2_t hi = __builtin_elementwise_max(ta, tb), lo = __builtin_elementwise_min(ta, tb);
+          smax[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, smax[e]), hi));
+          smin[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(s16x2_t, smin[e]), lo));
+          const uint32_t f0 = __builtin_amdgcn_perm(b[e], a[e], 0x05040100u);   // feature 2e of both rows
+          const uint32_t f1 = __builtin_amdgcn_perm(b[e], a[e], 0x07060302u);   // feature 2e+1 of both rows
+          sm[2 * e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f0), ones, sm[2 * e], false);
+          sm[2 * e + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f1), ones, sm[2 * e + 1], false);
+        }
+      }
+    }
+  };
+  auto finish_block = [&](int n, int j) {
+    // combine the 4 row groups of the wave, write the block's pooled vector, reset
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s16x2_t x = __builtin_bit_cast(s16x2_t, smax[e]), y = __builtin_bit_cast(s16x2_t, smin[e]);
+      x = __builtin_elementwise_max(x, __builtin_bit_cast(s16x2_t, (uint32_t)__shfl_xor((int)__builtin_bit_cast(uint32_t, x), 16)));
+      x = __builtin_elementwise_max(x, __builtin_bit_cast(s16x2_t, (uint32_t)__shfl_xor((int)__builtin_bit_cast(uint32_t, x), 32)));
+      y = __builtin_elementwise_min(y, __builtin_bit_cast(s16x2_t, (uint32_t)__shfl_xor((int)__builtin_bit_cast(uint32_t, y), 16)));
+      y = __builtin_elementwise_min(y, __builtin_bit_cast(s16x2_t, (uint32_t)__shfl_xor((int)__builtin_bit_cast(uint32_t, y), 32)));
+      smax[e] = __builtin_bit_cast(uint32_t, x);
+      smin[e] = __builtin_bit_cast(uint32_t, y);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { sm[e] += __shfl_xor(sm[e], 16); sm[e] += __shfl_xor(sm[e], 32); }
+    if (q4 == 0) {
+      uint32_t pmx[4], pmn[4], phi[4], plo[4];
+      const float inv = 1.0f / (float)bs;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pmx[e] = (j < j1) ? sortable(smax[e]) : 0u;             // back to bf16 patterns (exact values)
+        pmn[e] = (j < j1) ? sortable(smin[e]) : 0u;
+        const float v0 = sm[2 * e] * inv, v1 = sm[2 * e + 1] * inv;
+        const uint16_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
+        const float r0 = v0 - __uint_as_float((uint32_t)h0 << 16), r1 = v1 - __uint_as_float((uint32_t)h1 << 16);
+        phi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        plo[e] = pack2_bf16_rne(r0, r1);
+      }
+      // U[n][part*128 + 8*n16 .. +8]: 16-byte chunk index part*16 + n16, swizzled with n
+      unsigned char* row = u_lds + n * 1024;
+      *reinterpret_cast<uint4*>(row + (((0 * 16 + n16) ^ n) << 4)) = make_uint4(pmx[0], pmx[1], pmx[2], pmx[3]);
+      *reinterpret_cast<uint4*>(row + (((1 * 16 + n16) ^ n) << 4)) = make_uint4(pmn[0], pmn[1], pmn[2], pmn[3]);
+      *reinterpret_cast<uint4*>(row + (((2 * 16 + n16) ^ n) << 4)) = make_uint4(phi[0], phi[1], phi[2], phi[3]);
+      *reinterpret_cast<uint4*>(row + (((3 * 16 + n16) ^ n) << 4)) = make_uint4(plo[0], plo[1], plo[2], plo[3]);
+    }
+    reset_stats();
+  };
+  auto process_chunk = [&](const uint4 (&r)[8], int ch) {
     const int bb = ch / trips, trip = ch - bb * trips;
-    const int n = 4 * wave + bb;
-    const int j = jt + n;
-    const int t = q4 + 32 * trip;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (t + 4 * u < bs) {
-        const uint32_t w[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float a = bf16_lo(w[e]), b = bf16_hi(w[e]);
-          mx[2 * e] = fmaxf(mx[2 * e], a); mx[2 * e + 1] = fmaxf(mx[2 * e + 1], b);
-          mn[2 * e] = fminf(mn[2 * e], a); mn[2 * e + 1] = fminf(mn[2 * e + 1], b);
-          sm[2 * e] += a; sm[2 * e + 1] += b;
-        }
-      }
-    }
-    if (trip == trips - 1) {
-      // block complete: combine the 4 row groups of the wave, write its pooled vector, reset
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32));
-        mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16)); mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32));
-        sm[e] += __shfl_xor(sm[e], 16); sm[e] += __shfl_xor(sm[e], 32);
-      }
-      if (q4 == 0) {
-        uint32_t pmx[4], pmn[4], phi[4], plo[4];
-        const float inv = 1.0f / (float)bs;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float a0 = mx[2 * e], a1 = mx[2 * e + 1], b0 = mn[2 * e], b1 = mn[2 * e + 1];
-          if (j >= j1) { a0 = a1 = b0 = b1 = 0.f; }
-          pmx[e] = (__float_as_uint(a0) >> 16) | (__float_as_uint(a1) & 0xffff0000u);   // exact bf16 values
-          pmn[e] = (__float_as_uint(b0) >> 16) | (__float_as_uint(b1) & 0xffff0000u);
-          const float v0 = sm[2 * e] * inv, v1 = sm[2 * e + 1] * inv;
-          const uint16_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1);
-          const float r0 = v0 - __uint_as_float((uint32_t)h0 << 16), r1 = v1 - __uint_as_float((uint32_t)h1 << 16);
-          phi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          plo[e] = pack2_bf16_rne(r0, r1);
-        }
-        // U[n][part*128 + 8*n16 .. +8]: 16-byte chunk index part*16 + n16, swizzled with n
-        unsigned char* row = u_lds + n * 1024;
-        *reinterpret_cast<uint4*>(row + (((0 * 16 + n16) ^ n) << 4)) = make_uint4(pmx[0], pmx[1], pmx[2], pmx[3]);
-        *reinterpret_cast<uint4*>(row + (((1 * 16 + n16) ^ n) << 4)) = make_uint4(pmn[0], pmn[1], pmn[2], pmn[3]);
-        *reinterpret_cast<uint4*>(row + (((2 * 16 + n16) ^ n) << 4)) = make_uint4(phi[0], phi[1], phi[2], phi[3]);
-        *reinterpret_cast<uint4*>(row + (((3 * 16 + n16) ^ n) << 4)) = make_uint4(plo[0], plo[1], plo[2], plo[3]);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { mx[e] = -INFINITY; mn[e] = INFINITY; sm[e] = 0.f; }
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
+    const int rows_left = (bs - 32 * trip + 3 - q4) >> 2;        // rows of this lane still in the block
+    reduce_rows(r, rows_left >= 8 ? 8 : 4);                       // block sizes are multiples of 16
+    if (trip == trips - 1) finish_block(4 * wave + bb, jt + 4 * wave + bb);
+  };
+
+  reset_stats();
+  uint4 bufa[8], bufb[8];                      // ping-pong: the next chunk is in flight while one is reduced
+  load_chunk(bufa, 0);
+  for (int ch = 0; ch < nchunks; ch += 2) {    // nchunks = 4 * trips is even
+    load_chunk(bufb, ch + 1);
+    process_chunk(bufa, ch);
+    if (ch + 2 < nchunks) load_chunk(bufa, ch + 2);
+    process_chunk(bufb, ch + 1);
   }
   __syncthreads();
 
