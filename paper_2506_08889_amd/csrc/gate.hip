@@ -84,10 +84,18 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
 //   run of block ids, counts its hits, one work-group scan gives its offset.
 // ---------------------------------------------------------------------------------------
 constexpr int kSelectLdsBlocks = 8192;
+constexpr int kLinBins = 1024;    // top-k fast path: bins over [min score, max score]
+constexpr int kMaxCand = 256;     // ... and the most blocks its boundary bin may hold
 
 __device__ __forceinline__ uint64_t score_key(double s) {
   const uint64_t b = (uint64_t)__double_as_longlong(s);
   return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+
+// Linear bin of a score between the group's minimum and maximum: monotone non-decreasing in s.
+__device__ __forceinline__ int lin_bin_of(double s, double lo, double scale) {
+  const int b = (int)__dmul_rn(__dsub_rn(s, lo), scale);
+  return b < 0 ? 0 : (b > kLinBins - 1 ? kLinBins - 1 : b);
 }
 
 __device__ __forceinline__ double wg_reduce_max(double x, double* sm) {
@@ -147,6 +155,10 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   __shared__ int wcnt[8];
   __shared__ int digit_sel[3];
   __shared__ double red[4];
+  __shared__ int lin_hist[kLinBins];           // top-k fast path: linear-bin histogram
+  __shared__ unsigned long long cand_key[kMaxCand];
+  __shared__ int cand_idx[kMaxCand];
+  __shared__ int cand_n;
 
   const int i = blockIdx.y, h = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -220,6 +232,9 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   int from_full = 0;
   bool force_last = partial;
   double m = 0.0, Z = 1.0;
+  bool lin_fast = false;   // top-k fast path taken: selected = bin above lin_sel, or flagged inside it
+  int lin_sel = 0;
+  double lin_lo = 0.0, lin_scale = 0.0;
 
   if (p.mode == 0) {
     long long k = p.budget_blocks ? (long long)p.budget_blocks[i]
@@ -235,7 +250,77 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     if (from_full >= nfull) {
       T = 0;               // every full block is taken
       take_ge = true;
-    } else if (from_full > 0) {
+    } else if (from_full > 0 && SRC != 0) {
+      // Fast path.  Scores are binned linearly between their minimum and maximum (monotone in
+      // the score, and unlike the leading bits of a float it spreads the blocks evenly, so the
+      // LDS atomics do not pile up); one scan finds the bin that holds the k-th largest score;
+      // every block in a higher bin is selected, and the few blocks inside the boundary bin are
+      // ranked exactly (key, then lower index) against each other.  Falls through to the radix
+      // walk when that bin is crowded (many equal or nearly equal scores).
+      double lo = INFINITY, hi = -INFINITY;
+      for (int j = tid; j < nfull; j += 256) { const double v = sc[j]; lo = fmin(lo, v); hi = fmax(hi, v); }
+      hi = wg_reduce_max(hi, red);
+      lo = -wg_reduce_max(-lo, red);
+      const double scale = __ddiv_rn((double)kLinBins, __dsub_rn(hi, lo));
+      if (hi > lo && scale > 0.0 && scale < 1.0e300) {
+        for (int b = tid; b < kLinBins; b += 256) lin_hist[b] = 0;
+        if (tid == 0) cand_n = 0;
+        unsigned char* flags = dyn_smem + (size_t)p.nb_max * sizeof(double);
+        for (int j = tid; j < nfull; j += 256) flags[j] = 0;
+        __syncthreads();
+        for (int j = tid; j < nfull; j += 256) atomicAdd(&lin_hist[lin_bin_of(sc[j], lo, scale)], 1);
+        __syncthreads();
+        // thread t owns bins 1023-4t .. 1020-4t (descending); exclusive scan of the counts from the top
+        const int b0 = kLinBins - 1 - 4 * tid;
+        const int c0 = lin_hist[b0], c1 = lin_hist[b0 - 1], c2 = lin_hist[b0 - 2], c3 = lin_hist[b0 - 3];
+        int above, dummy_e, tot, dummy_t;
+        wg_exclusive_scan2(c0 + c1 + c2 + c3, 0, wcnt, &above, &dummy_e, &tot, &dummy_t);
+        if (above < from_full && from_full <= above + c0 + c1 + c2 + c3) {   // exactly one thread
+          int bsel = b0, cnt = c0;
+          if (from_full > above + c0) {
+            above += c0; bsel = b0 - 1; cnt = c1;
+            if (from_full > above + c1) {
+              above += c1; bsel = b0 - 2; cnt = c2;
+              if (from_full > above + c2) { above += c2; bsel = b0 - 3; cnt = c3; }
+            }
+          }
+          digit_sel[0] = bsel;
+          digit_sel[1] = from_full - above;     // blocks still needed from the boundary bin
+          digit_sel[2] = cnt;                   // blocks in the boundary bin
+        }
+        __syncthreads();
+        lin_sel = digit_sel[0];
+        const int need = digit_sel[1], cnt = digit_sel[2];
+        if (cnt <= kMaxCand) {
+          for (int j = tid; j < nfull; j += 256) {
+            const double v = sc[j];
+            if (lin_bin_of(v, lo, scale) == lin_sel) {
+              const int at = atomicAdd(&cand_n, 1);
+              cand_key[at] = score_key(v);
+              cand_idx[at] = j;
+            }
+          }
+          __syncthreads();
+          if (tid < cnt) {
+            const unsigned long long mk = cand_key[tid];
+            const int mi = cand_idx[tid];
+            int rank = 0;
+            for (int u = 0; u < cnt; ++u) {
+              const unsigned long long uk = cand_key[u];
+              rank += (uk > mk) || (uk == mk && cand_idx[u] < mi);
+            }
+            if (rank < need) flags[mi] = 1;
+          }
+          __syncthreads();
+          lin_lo = lo;
+          lin_scale = scale;
+          lin_fast = true;
+        } else {
+          __syncthreads();
+        }
+      }
+    }
+    if (from_full > 0 && from_full < nfull && !lin_fast) {
       uint64_t prefix = 0, mask = 0;
       int remaining = from_full;
       for (int pass = 7; pass >= 0; --pass) {
@@ -378,12 +463,17 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   const bool any_full = (p.mode == 0) ? (from_full > 0) : (nfull > 0);
   int n = 0;
   if (any_full) {
-    const int run = (nfull + 255) / 256;
+    const int run = ((nfull + 255) / 256) | 1;   // odd run length: consecutive threads then start in different LDS banks
     const int j0 = tid * run;
     const int j1 = (j0 + run < nfull) ? j0 + run : nfull;
     auto classify = [&](int j, bool* gt, bool* eq) {
       const double s = sc[j];
-      if (p.mode != 1) {
+      if (lin_fast) {
+        const int b = lin_bin_of(s, lin_lo, lin_scale);
+        const unsigned char* flags = dyn_smem + (size_t)p.nb_max * sizeof(double);
+        *gt = b > lin_sel || (b == lin_sel && flags[j] != 0);
+        *eq = false;
+      } else if (p.mode != 1) {
         const uint64_t key = score_key(s);
         *gt = take_ge ? key >= T : key > T;
         *eq = !take_ge && key == T;
@@ -434,7 +524,7 @@ hipError_t launch_gate_score(const GateParams& p, hipStream_t s) {
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
   if (p.nb_max <= kSelectLdsBlocks)
-    hipLaunchKernelGGL(seer_gate_select_kernel<1>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
+    hipLaunchKernelGGL(seer_gate_select_kernel<1>, grid, dim3(256), (size_t)p.nb_max * (sizeof(double) + 1), s, p);
   else
     hipLaunchKernelGGL(seer_gate_select_kernel<0>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
@@ -444,7 +534,7 @@ bool gate_fused_possible(const GateParams& p) { return p.nb_max <= kSelectLdsBlo
 
 hipError_t launch_gate_fused(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
-  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), (size_t)p.nb_max * sizeof(double), s, p);
+  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), (size_t)p.nb_max * (sizeof(double) + 1), s, p);
   return hipGetLastError();
 }
 
