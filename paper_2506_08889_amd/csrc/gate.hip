@@ -1,5 +1,5 @@
 // AttnGate block selection on gfx950: gate scores against the K Compression Cache (Eq. 1c,
-// Sec. 3.2) and token-budget top-k / threshold selection (Sec. 3.1).
+// Sec. 3.2) and token-budget top-k / threshold selection (Sec. 3.1), plus top-p (Sec. 6.2).
 //
 // Scores are accumulated in fp64 from exactly converted bf16 inputs: a bf16 x bf16 product
 // has a 16-bit significand, so each fp64 FMA adds an exact product and the sum is the exact
@@ -71,15 +71,20 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
 
 // ---------------------------------------------------------------------------------------
 // Select kernel: one work-group per (sequence, kv head).  The scores of the group are first
-// copied into LDS (up to kSelectLdsBlocks of them; longer caches are re-read from L2).
-//   top-k:     radix select over order-preserving 64-bit keys, 8 bits per pass from the top:
-//              LDS histogram of the still-undecided candidates, then the first wave scans the
-//              256 bins (4 per lane, descending) and picks the digit that holds the k-th
-//              largest key.  The search stops as soon as every candidate left in that bin is
-//              needed (normally after 3-4 passes on real-valued scores); after all 8 passes the
-//              k-th key is known exactly and `need_eq` of its duplicates are taken, lowest
+// brought into LDS (up to kSelectLdsBlocks of them; longer caches are re-read from L2).
+//   top-k:     fast path - scores binned linearly between their minimum and maximum (monotone,
+//              and evenly filled, so LDS atomics do not pile up), one scan finds the bin holding
+//              the k-th largest score, blocks in higher bins are taken and the few blocks of the
+//              boundary bin are ranked exactly against each other (key, then lower index).
+//              Fallback (crowded boundary bin, i.e. many equal scores; or scores left in global
+//              memory) - radix select over order-preserving 64-bit keys, 8 bits per pass from the
+//              top: LDS histogram of the still-undecided candidates, the first wave scans the 256
+//              bins (4 per lane, descending) and picks the digit that holds the k-th largest key;
+//              it stops as soon as every candidate left in that bin is needed; after all 8 passes
+//              the k-th key is known exactly and `need_eq` of its duplicates are taken, lowest
 //              index first.
 //   threshold: fp64 softmax over the full blocks (max, sum of exp, divide), S_j > tau.
+//   top-p:     the radix walk steered by probability mass (2^-62 fixed point, exact sums).
 //   Either way an ordered compaction emits the ascending list: each thread owns a contiguous
 //   run of block ids, counts its hits, one work-group scan gives its offset.
 // ---------------------------------------------------------------------------------------
