@@ -17,7 +17,7 @@
 //                 wave-private, XOR-swizzled LDS tile and read back in operand layout.
 //   softmax       D gives each lane 4 tokens of one head (x2 tiles): max over the lane's 8
 //                 values and across q (2 shuffles); exponentials in the base-2 domain.
-//   O^T = V^T P^T B = P^T is exactly the layout D left the probabilities in (tile 0 -> k slots
+//   O^T = V^T P^T B = P^T (as hi + lo bf16 terms) is exactly the layout D left the probabilities in (tile 0 -> k slots
 //                 0..3, tile 1 -> k slots 4..7 of each lane), so P never moves.  A = V^T needs,
 //                 per lane, 8 tokens of one feature: each lane loads 8 rows x 16 bytes (again
 //                 fully coalesced), and 32 in-lane 16-bit interleaves build the 8 operands;
@@ -288,11 +288,20 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 #pragma unroll
       for (int e = 0; e < 8; ++e) oacc[e] *= alpha;
     }
-    uint4 pb;
-    pb.x = pack_bf16(pr[0], pr[1]);
-    pb.y = pack_bf16(pr[2], pr[3]);
-    pb.z = pack_bf16(pr[4], pr[5]);
-    pb.w = pack_bf16(pr[6], pr[7]);
+    // Probabilities enter the bf16 MFMA as two terms, p = hi + lo (hi = bf16(p), lo = bf16(p - hi)),
+    // so the PV product carries ~16 mantissa bits instead of 8; the second MFMA per operand is free
+    // at this arithmetic intensity.
+    uint4 pb, pl;
+    {
+      uint32_t h[4], l[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        h[c] = pack_bf16(pr[2 * c], pr[2 * c + 1]);
+        l[c] = pack_bf16(pr[2 * c] - __uint_as_float(h[c] << 16), pr[2 * c + 1] - __uint_as_float(h[c] & 0xffff0000u));
+      }
+      pb = make_uint4(h[0], h[1], h[2], h[3]);
+      pl = make_uint4(l[0], l[1], l[2], l[3]);
+    }
 
     // ---- 4. O^T += V^T P^T ----------------------------------------------------------------------
 #pragma unroll
@@ -306,6 +315,8 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
       const uint4 va = make_uint4(o[0], o[1], o[2], o[3]);
       oacc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va),
                                                         __builtin_bit_cast(bf16x8_t, pb), oacc[e], 0, 0, 0);
+      oacc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va),
+                                                        __builtin_bit_cast(bf16x8_t, pl), oacc[e], 0, 0, 0);
     }
     if (nxt.ntok > 0) load_v(nxt);
     cur = nxt;

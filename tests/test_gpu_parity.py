@@ -459,3 +459,54 @@ def test_top_p_selection_and_decode(bs):
         ri, rc = oracle.gate_select(qg, kc, sl, bs, mode=oracle.SELECT_TOPP, threshold=p, max_sel=40)
         gi, gc = gate_both_impls(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, mode=seer.SELECT_TOPP, threshold=p, max_sel=40)
         check_indices(gi[1:], gc[1:], ri[1:], rc[1:], what=f"top-p ties p={p}")
+
+
+def test_randomised_shapes_gate_and_decode():
+    """Forty seeded random configurations (group size, block size, batch, lengths incl. empty and
+    sub-block sequences, contiguous/paged, selection mode, split plan): indices bit-exact, outputs
+    within the tight fp32-output bars."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        g = int(rng.integers(1, 9))
+        Hkv = int(rng.choice([1, 2, 3, 8]))
+        bs = int(rng.choice([32, 64, 128]))
+        B = int(rng.integers(1, 6))
+        paged = bool(rng.integers(0, 2))
+        hi = int(rng.choice([bs * 3, bs * 20, bs * 70]))
+        w = synth.Workload(f"rand{case}", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen_range=(1, hi),
+                           seqlen_dist="uniform", paged=paged, budget_tokens=0, budget_frac=float(rng.choice([0.1, 0.3, 1.0])),
+                           seed=1000 + case)
+        inp = synth.make_inputs(w, DEV)
+        # some sequences empty or shorter than a block
+        sl = inp.seqlens_cpu.clone()
+        if B > 1 and case % 3 == 0:
+            sl[0] = int(rng.choice([0, 1, bs - 1, bs]))
+        inp.seqlens_cpu = sl
+        inp.seqlens = sl.to(DEV)
+        mode = [seer.SELECT_TOPK, seer.SELECT_THRESHOLD, seer.SELECT_TOPP][case % 3]
+        max_sel = inp.nb_max if mode != seer.SELECT_TOPK else inp.max_sel
+        thr = 0.0
+        if mode != seer.SELECT_TOPK:
+            _, _, scores = oracle_gate(inp, return_scores=True)
+            if (sl // bs).max() == 0:
+                mode, max_sel = seer.SELECT_TOPK, inp.max_sel
+            elif mode == seer.SELECT_THRESHOLD:
+                thr = pick_threshold(scores, sl, bs, w.Dg, float(rng.choice([0.5, 0.2])))
+            else:
+                thr = pick_top_p(scores, sl, bs, w.Dg, 0.3, 0.9, seed=case)
+        print(f"[rand {case}] g={g} Hkv={Hkv} bs={bs} B={B} paged={paged} mode={mode} seqlens={sl.tolist()}", flush=True)
+        ref_idx, ref_cnt = oracle_gate(inp, mode=mode, threshold=thr, max_sel=max_sel)
+        gi, gc = gpu_gate(inp, mode=mode, threshold=thr, max_sel=max_sel)
+        check_indices(gi, gc, ref_idx, ref_cnt, what=f"rand {case} gate")
+        ref_out, ref_lse = oracle_decode(inp, ref_idx, ref_cnt)
+        seer.set_knob(1, int(rng.choice([0, 1, 2, 7])))
+        seer.set_knob(2, int(rng.integers(0, 2)))
+        out, lse = gpu_decode(inp, gi, gc, torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"rand {case} decode")
+        seer.set_knob(1, 0)
+        dref_out, dref_lse = oracle_decode(inp, None, None)
+        out, lse = seer.dense_decode(inp.q, inp.k, inp.v, inp.seqlens, inp.nb_max, bs, w.scale,
+                                     page_table=inp.page_table, page_size=inp.page_size, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out, lse, dref_out, dref_lse, tight=True, what=f"rand {case} dense")
