@@ -153,6 +153,25 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv /* host s
                                float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Several new tokens per sequence in one call - the multi-token / speculative decoding direction of
+ * Sec. 6.3, where the q_len x g query rows of a kv head fill the matrix-core tile that a single
+ * token leaves mostly empty.  The q_len queries of sequence i are its last q_len tokens (positions
+ * seqlens[i]-q_len .. seqlens[i]-1; seqlens counts them, their K/V are already in the cache); query t
+ * attends the cached tokens up to and including its own position, restricted to the listed blocks;
+ * one list per (sequence, kv head) is shared by the q_len queries (how a gate combines the
+ * selections of several queries is left to the caller).  Query t alone equals seer_sparse_decode on a
+ * sequence of length seqlens[i]-q_len+1+t.
+ * q bf16 [B,q_len,Hq,d]; out [B,q_len,Hq,d]; lse fp32 [B,q_len,Hq].  q_len * (Hq/Hkv) <= 16 and
+ * block_size a multiple of 32 (SEER_ERR_UNSUPPORTED otherwise).  Workspace:
+ * seer_decode_workspace_bytes(B, q_len*Hq, Hkv, d, max_sel).
+ */
+seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv /* host struct */,
+                                     const int32_t* seqlens, const int32_t* block_idx, const int32_t* nblk,
+                                     int max_sel, int B, int q_len, int Hq, int Hkv, int d, int block_size,
+                                     float scale, void* out, seer_dtype out_dtype, float* lse,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dense flash-decode over all ceil(seqlens[i]/block_size) blocks of every sequence: the
  * baseline the sparse kernel's speed-up is measured against (Sec. 4.4).  max_blocks >= the
  * largest block count of any sequence (blocks beyond it are not visited).

@@ -70,6 +70,11 @@ def _load():
             ctypes.c_void_p, ctypes.POINTER(_KV), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_sparse_decode_multi.restype = ctypes.c_int
+        lib.oracle_sparse_decode_multi.argtypes = [
+            ctypes.c_void_p, ctypes.POINTER(_KV), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_gate_q.restype = ctypes.c_int
         lib.oracle_gate_q.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int, ctypes.c_void_p] + [ctypes.c_int] * 5 + \
             [ctypes.c_void_p, ctypes.c_void_p]
@@ -273,3 +278,26 @@ def kc_update(k_nope, wk, rope_cos, rope_sin, seqlens, block_size: int, nb_max: 
     if rc != 0:
         raise ValueError(f"oracle_kc_update failed ({rc})")
     return out, out_bits
+
+
+def sparse_decode_multi(q, kv: KVLayout, seqlens, block_idx, nblk, block_size: int, scale: float):
+    """T new tokens per sequence in one step (Sec. 6.3 direction): q [B,T,Hq,d] bf16, the queries are
+    the last T tokens of each sequence, causal among themselves, one block list per (sequence, kv
+    head).  Returns (out [B,T,Hq,d] fp64, lse [B,T,Hq] fp64)."""
+    lib = _load()
+    qb = np.ascontiguousarray(_bits(q))
+    B, T, Hq, d = qb.shape
+    kb, vb = _bits(kv.k), _bits(kv.v)
+    assert kb.shape == vb.shape and kb.strides == vb.strides and kb.shape[3] == d
+    Hkv = kb.shape[1]
+    st, _, pt = _kv_struct(kv.k, kv.page_table, kv.page_size, B)
+    st.v = vb.ctypes.data
+    sl, bi, nk = _i32(seqlens), _i32(block_idx), _i32(nblk)
+    max_sel = bi.shape[2] if bi is not None else 0
+    out = np.full((B, T, Hq, d), np.nan, dtype=np.float64)
+    lse = np.full((B, T, Hq), np.nan, dtype=np.float64)
+    rc = lib.oracle_sparse_decode_multi(_ptr(qb), ctypes.byref(st), _ptr(sl), _ptr(bi), _ptr(nk), max_sel, B, T,
+                                        Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out), _ptr(lse), None)
+    if rc != 0:
+        raise ValueError("oracle_sparse_decode_multi: bad sizes")
+    return out, lse

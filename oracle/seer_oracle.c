@@ -216,6 +216,11 @@ static int64_t token_offset(const oracle_kv_t* kv, int i, int hk, int64_t t) {
  * set gives out = 0 and lse = -inf.
  * group_filter (optional, [B*Hkv] bytes): groups with 0 are left untouched.
  */
+int oracle_sparse_decode_multi(const uint16_t* q, const oracle_kv_t* kv, const int32_t* seqlens,
+                               const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int T,
+                               int Hq, int Hkv, int d, int block_size, float scale, double* out, double* lse,
+                               const uint8_t* group_filter);
+
 int oracle_sparse_decode(const uint16_t* q, const oracle_kv_t* kv, const int32_t* seqlens,
                          const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int Hq,
                          int Hkv, int d, int block_size, float scale, double* out, double* lse,
@@ -413,4 +418,71 @@ int oracle_kc_update(const oracle_kv_t* kv, const uint16_t* wk, const float* rop
       free(y);
     }
   return bad ? -2 : 0;
+}
+
+
+/*
+ * Several new tokens per sequence in one step (the multi-token / speculative decoding direction of
+ * Sec. 6.3): the T queries of sequence i are its last T tokens, at positions S-T .. S-1 (S =
+ * seqlens[i] counts them); query t attends the cached tokens up to and including its own position,
+ * restricted to the listed blocks - one list per (sequence, kv head), shared by the T queries.
+ * q [B,T,Hq,d]; out [B,T,Hq,d]; lse [B,T,Hq].  Query t is exactly a single-token decode of a
+ * sequence of length S-T+1+t with the same list.
+ */
+int oracle_sparse_decode_multi(const uint16_t* q, const oracle_kv_t* kv, const int32_t* seqlens,
+                               const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int T,
+                               int Hq, int Hkv, int d, int block_size, float scale, double* out, double* lse,
+                               const uint8_t* group_filter) {
+  if (Hkv <= 0 || Hq % Hkv || T <= 0) return -1;
+  const int g = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+  for (int i = 0; i < B; ++i) {
+    for (int hk = 0; hk < Hkv; ++hk) {
+      const int64_t grp = (int64_t)i * Hkv + hk;
+      if (group_filter && !group_filter[grp]) continue;
+      int S = seqlens[i];
+      if (S < 0) S = 0;
+      const int nb = (S + block_size - 1) / block_size;
+      int nlist = block_idx ? nblk[grp] : nb;
+      if (nlist < 0) nlist = 0;
+      if (block_idx && nlist > max_sel) nlist = max_sel;
+      for (int t = 0; t < T; ++t) {
+        const int64_t limit = (int64_t)S - (T - 1 - t);        /* tokens [0, limit) are visible to query t */
+        for (int hh = 0; hh < g; ++hh) {
+          const int h = hk * g + hh;
+          const int64_t row = ((int64_t)i * T + t) * Hq + h;
+          const uint16_t* qrow = q + row * d;
+          double* orow = out + row * d;
+          for (int c = 0; c < d; ++c) orow[c] = 0.0;
+          /* pass 1: max; pass 2: sums (token lists are short enough to recompute the logits) */
+          double m = -INFINITY, Z = 0.0;
+          for (int pass = 0; pass < 2; ++pass) {
+            for (int p = 0; p < nlist; ++p) {
+              const int j = block_idx ? block_idx[grp * max_sel + p] : p;
+              if (j < 0 || j >= nb) continue;
+              int64_t t1 = (int64_t)(j + 1) * block_size;
+              if (t1 > limit) t1 = limit;
+              for (int64_t tok = (int64_t)j * block_size; tok < t1; ++tok) {
+                const int64_t off = token_offset(kv, i, hk, tok);
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c) dot += bf16_value(qrow[c]) * bf16_value(kv->k[off + c]);
+                const double x = (double)scale * dot;
+                if (pass == 0) { if (x > m) m = x; }
+                else {
+                  const double e = exp(x - m);
+                  Z += e;
+                  for (int c = 0; c < d; ++c) orow[c] += e * bf16_value(kv->v[off + c]);
+                }
+              }
+            }
+            if (pass == 0 && m == -INFINITY) break;
+          }
+          if (m == -INFINITY) { lse[row] = -INFINITY; continue; }
+          for (int c = 0; c < d; ++c) orow[c] /= Z;
+          lse[row] = m + log(Z);
+        }
+      }
+    }
+  }
+  return 0;
 }

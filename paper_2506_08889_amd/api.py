@@ -73,6 +73,10 @@ def load_library():
     lib.seer_sparse_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int,
                                        c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
                                        c_vp, c_sz, c_vp]
+    lib.seer_sparse_decode_multi.restype = c_int
+    lib.seer_sparse_decode_multi.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int, c_int,
+                                             c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
+                                             c_vp, c_sz, c_vp]
     lib.seer_dense_decode.restype = c_int
     lib.seer_dense_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int,
                                       c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
@@ -231,6 +235,36 @@ def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: to
                                 0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
                                 workspace.numel(), _stream())
     _check("seer_sparse_decode", st)
+    return out, lse
+
+
+def sparse_decode_multi(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor,
+                        block_idx: torch.Tensor, nblk: torch.Tensor, block_size: int, scale: float, *,
+                        page_table: Optional[torch.Tensor] = None, page_size: int = 0,
+                        out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                        out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+    """seer_sparse_decode_multi.  q [B,q_len,Hq,d] bf16 (the last q_len tokens of each sequence).
+    Returns (out [B,q_len,Hq,d], lse [B,q_len,Hq] fp32)."""
+    lib = load_library()
+    _want(q, torch.bfloat16, "q"); _want(seqlens, torch.int32, "seqlens")
+    _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk")
+    if q.dim() != 4 or not (q.is_contiguous() and block_idx.is_contiguous() and nblk.is_contiguous()):
+        raise ValueError("q must be contiguous [B,q_len,Hq,d]; block_idx and nblk contiguous")
+    B, T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    max_sel = block_idx.shape[2]
+    lay = _layout(k, v, page_table, page_size)
+    if out is None:
+        out = torch.empty(B, T, Hq, d, dtype=out_dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, T, Hq, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _workspace(decode_workspace_bytes(B, Hq * T, Hkv, d, max_sel), q.device)
+    st = lib.seer_sparse_decode_multi(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
+                                      max_sel, B, T, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
+                                      0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
+                                      workspace.numel(), _stream())
+    _check("seer_sparse_decode_multi", st)
     return out, lse
 
 

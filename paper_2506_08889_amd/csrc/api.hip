@@ -111,17 +111,21 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
                           const int32_t* block_idx, const int32_t* nblk, int max_blocks, bool sparse,
-                          int B, int Hq, int Hkv, int d, int block_size, float scale, void* out,
+                          int B, int q_len, int Hq, int Hkv, int d, int block_size, float scale, void* out,
                           seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                           void* stream) {
   if (!q || !kv || !seqlens || !out) return SEER_ERR_NULL;
   if (!kv->k || !kv->v) return SEER_ERR_NULL;
   if (sparse && (!block_idx || !nblk)) return SEER_ERR_NULL;
-  if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || d <= 0 || block_size <= 0) return SEER_ERR_SHAPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || d <= 0 || block_size <= 0 || q_len <= 0)
+    return SEER_ERR_SHAPE;
   if (Hq % Hkv != 0) return SEER_ERR_SHAPE;
   if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
   const int g = Hq / Hkv;
+  const int rows = g * q_len;
   if (d != seer::kHeadDim || g > seer::kMaxGroup || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  // several new tokens share the MFMA tile with the heads of the group: 16 rows, MFMA kernel only
+  if (q_len > 1 && (rows > seer::kMaxRows || block_size % 32 != 0 || g_knob_impl == 1)) return SEER_ERR_UNSUPPORTED;
   if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
   if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
     return SEER_ERR_SHAPE;
@@ -131,7 +135,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   }
   int ns, len;
   plan_splits(B, Hkv, max_blocks, block_size, &ns, &len);
-  const size_t need = decode_ws_bytes(B, Hkv, g, max_splits_for(max_blocks));
+  const size_t need = decode_ws_bytes(B, Hkv, rows, max_splits_for(max_blocks));
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SEER_ERR_WORKSPACE;
 
@@ -150,10 +154,12 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   p.nblk = sparse ? nblk : nullptr;
   p.max_blocks = max_blocks;
   p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.g = g; p.block_size = block_size;
+  p.q_len = q_len;
+  p.rows = rows;
   p.scale_log2e = (float)((double)scale * 1.4426950408889634);
   p.num_splits = ns;
   p.blocks_per_split = len;
-  const size_t parts = (size_t)B * Hkv * ns * g;
+  const size_t parts = (size_t)B * Hkv * ns * rows;
   p.part_acc = static_cast<float*>(workspace);
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) +
                                        align_up(parts * seer::kHeadDim * sizeof(float), 256));
@@ -206,7 +212,8 @@ seer_status seer_gate_workspace_bytes(int B, int Hkv, int nb_max, size_t* bytes)
 seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_blocks, size_t* bytes) {
   if (!bytes) return SEER_ERR_NULL;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || max_blocks <= 0 || Hq % Hkv) return SEER_ERR_SHAPE;
-  if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup) return SEER_ERR_UNSUPPORTED;
+  // Hq may be q_len * (query heads) for seer_sparse_decode_multi: up to 16 rows per kv head
+  if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxRows) return SEER_ERR_UNSUPPORTED;
   *bytes = decode_ws_bytes(B, Hkv, Hq / Hkv, max_splits_for(max_blocks));
   return SEER_OK;
 }
@@ -288,7 +295,16 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv, const in
                                int Hkv, int d, int block_size, float scale, void* out,
                                seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                                void* stream) {
-  return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, Hq, Hkv, d, block_size, scale,
+  return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, 1, Hq, Hkv, d, block_size, scale,
+                       out, out_dtype, lse, workspace, workspace_bytes, stream);
+}
+
+seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
+                                     const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int q_len,
+                                     int Hq, int Hkv, int d, int block_size, float scale, void* out,
+                                     seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, q_len, Hq, Hkv, d, block_size, scale,
                        out, out_dtype, lse, workspace, workspace_bytes, stream);
 }
 
@@ -296,7 +312,7 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int
                               int B, int Hq, int Hkv, int d, int block_size, float scale, void* out,
                               seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                               void* stream) {
-  return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, Hq, Hkv, d, block_size,
+  return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, 1, Hq, Hkv, d, block_size,
                        scale, out, out_dtype, lse, workspace, workspace_bytes, stream);
 }
 

@@ -2,7 +2,7 @@
 // block list is partitioned along num_split; each part leaves a running max m, a sum l and an
 // unnormalised output, combined here into out and lse).
 //
-// One work-group of 128 threads per query head.  The first wave reads the (m, l) pairs of all
+// One work-group of 128 threads per query row (head, or new token x head).  The first wave reads the (m, l) pairs of all
 // slices in parallel (one slice per lane), reduces the max and turns them into weights in LDS;
 // then thread dd accumulates feature dd over the slices with independent, unrolled loads.
 #include "seer_internal.h"
@@ -15,7 +15,7 @@ __global__ __launch_bounds__(128) void seer_decode_merge_kernel(DecodeParams p) 
   __shared__ float wgt[kMergeMaxSplits];
   __shared__ float tot[2];
 
-  const int g = p.g;
+  const int g = p.rows;            // rows of a group's tile (new tokens x heads)
   const int h = blockIdx.x % g, hk = blockIdx.x / g, i = blockIdx.y;
   int S = p.seqlens[i];
   S = S < 0 ? 0 : S;
@@ -69,12 +69,12 @@ __global__ __launch_bounds__(128) void seer_decode_merge_kernel(DecodeParams p) 
     a += a0 * wgt[s] + a1 * wgt[s + 1] + a2 * wgt[s + 2] + a3 * wgt[s + 3];
   }
   for (; s < nsv; ++s) a += pa[(int64_t)s * g * kHeadDim + tid] * wgt[s];
-  store_output(p, (int64_t)i * p.Hq + (int64_t)hk * g + h, tid, tot[0], tot[1], a);
+  store_output(p, output_row(p, i, hk, h), tid, tot[0], tot[1], a);
 }
 
 hipError_t launch_decode_merge(const DecodeParams& p, hipStream_t s) {
   if (p.num_splits > kMergeMaxSplits) return hipErrorInvalidValue;
-  dim3 grid(p.Hkv * p.g, p.B);
+  dim3 grid(p.Hkv * p.rows, p.B);
   hipLaunchKernelGGL(seer_decode_merge_kernel, grid, dim3(128), 0, s, p);
   return hipGetLastError();
 }

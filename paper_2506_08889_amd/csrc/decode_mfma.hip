@@ -39,6 +39,7 @@ namespace {
 struct HalfBlock {
   int64_t off;   // element offset of the first token of the half-block
   int ntok;      // valid tokens (1..32); 0 = no more work
+  int tok0;      // position of its first token in the sequence
 };
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }
@@ -62,13 +63,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 template <bool ROWS128>
 __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodeParams p) {
   // 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256 + 4 * kMaxRows * 2 * 4];
 
   int split, hk, i;
   decode_wg_coords(p, &split, &hk, &i);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
-  const int g = p.g;
+  const int g = p.g, rows = p.rows;
 
   const int bs = p.block_size;
   const int64_t grp = (int64_t)i * p.Hkv + hk;
@@ -121,19 +122,23 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   const int64_t st = ROWS128 ? (int64_t)kHeadDim : p.stride_token;
   pf_stage2();
 
-  // ---- Q^T operand: head n16 (zero rows for the padding heads) ---------------------------
+  // ---- Q^T operand: row n16 = (new token t, head h); zero rows for the padding ------------------
+  const int row_t = n16 / g, row_h = n16 - row_t * g;
   uint4 qb[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     qb[kk] = make_uint4(0, 0, 0, 0);
-    if (n16 < g)
+    if (n16 < rows)
       qb[kk] = *reinterpret_cast<const uint4*>(
-          p.q + ((int64_t)i * p.Hq + (int64_t)hk * g + n16) * kHeadDim + kk * 32 + q4 * 8);
+          p.q + (((int64_t)i * p.q_len + row_t) * p.Hq + (int64_t)hk * g + row_h) * kHeadDim + kk * 32 + q4 * 8);
   }
+  // Query t of q_len sees the tokens before position S - (q_len - 1 - t); with one new token that is S.
+  const int row_limit = (n16 < rows) ? S - (p.q_len - 1 - row_t) : S;
+  const int causal_from = S - p.q_len + 1;     // first position that is masked for some row
 
   int loaded_chunk = -1;
   int64_t d_off = 0;
-  int d_ntok = 0;
+  int d_ntok = 0, d_tok = 0;
   auto finalize_chunk = [&](int chunk) {
     if (pf_chunk != chunk) pf_stage1(chunk);
     if (pf_stage < 2) pf_stage2();
@@ -143,8 +148,10 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     if (ok && p.page_table) ok = ((int64_t)j * bs) / p.page_size < p.max_pages;
     d_off = 0;
     d_ntok = 0;
+    d_tok = 0;
     if (ok) {
       const int64_t t0 = (int64_t)j * bs;
+      d_tok = j * bs;
       d_off = p.page_table ? (int64_t)pg_pf * p.stride_seq + (int64_t)hk * p.stride_head + (t0 % p.page_size) * p.stride_token
                            : (int64_t)i * p.stride_seq + (int64_t)hk * p.stride_head + t0 * p.stride_token;
       d_ntok = (S - j * bs < bs) ? S - j * bs : bs;
@@ -157,6 +164,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     HalfBlock r;
     r.off = 0;
     r.ntok = 0;
+    r.tok0 = 0;
     while (hb < nh) {
       const int e = hb / hpb, half = hb - e * hpb;
       const int chunk = e >> 6;
@@ -170,12 +178,14 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
       const int nt_blk = __shfl(d_ntok, src);
       const int lo = __shfl((int)(uint32_t)(uint64_t)d_off, src);
       const int hi = __shfl((int)(uint32_t)((uint64_t)d_off >> 32), src);
+      const int tk = __shfl(d_tok, src);
       hb += 4;
       int nt = nt_blk - half * 32;
       nt = nt > 32 ? 32 : nt;
       if (nt > 0) {
         r.off = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo) + (int64_t)half * 32 * st;
         r.ntok = nt;
+        r.tok0 = tk + half * 32;
         return r;
       }
     }
@@ -264,22 +274,27 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[t][r] * p.scale_log2e;
-    if (cur.ntok < 32) {
+    if (cur.ntok < 32 || cur.tok0 + 32 > causal_from) {
+      // ragged tail of the sequence and / or the causal limit of this row among the new tokens
+      const int lim = (cur.ntok < row_limit - cur.tok0) ? cur.ntok : row_limit - cur.tok0;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          if (16 * t + 4 * q4 + r >= cur.ntok) x[4 * t + r] = -INFINITY;
+          if (16 * t + 4 * q4 + r >= lim) x[4 * t + r] = -INFINITY;
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);      // finite: token 0 of the half-block is always valid
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float m_new = fmaxf(m_run, mx);
+    // A row may have seen nothing yet (every token so far beyond its causal limit): keep the
+    // exponent arguments finite-or-minus-infinity, never inf - inf.
+    const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
     float pr[8], psum = 0.f;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-      pr[c] = __builtin_amdgcn_exp2f(x[c] - m_new);
+      pr[c] = __builtin_amdgcn_exp2f(x[c] - m_ref);
       psum += pr[c];
     }
     l_run = l_run * alpha + psum;
@@ -326,33 +341,33 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   __syncthreads();                                    // K tiles are dead from here on
-  float* sm_acc = reinterpret_cast<float*>(smem);     // [4][8][128]
-  float* sm_ml = sm_acc + 4 * kMaxGroup * kHeadDim;   // [4][8][2]  (16 KiB + 256 B <= 32 KiB)
-  if (n16 < g) {
-    float* dst = sm_acc + ((wave * kMaxGroup + n16) * kHeadDim) + 32 * q4;
+  float* sm_acc = reinterpret_cast<float*>(smem);     // [4][16][128] = the 32 KiB of the K tiles
+  float* sm_ml = sm_acc + 4 * kMaxRows * kHeadDim;    // [4][16][2]
+  if (n16 < rows) {
+    float* dst = sm_acc + ((wave * kMaxRows + n16) * kHeadDim) + 32 * q4;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int e = 0; e < 8; ++e) dst[8 * r + e] = oacc[e][r];
     if (q4 == 0) {
-      sm_ml[(wave * kMaxGroup + n16) * 2 + 0] = m_run;
-      sm_ml[(wave * kMaxGroup + n16) * 2 + 1] = l_run;
+      sm_ml[(wave * kMaxRows + n16) * 2 + 0] = m_run;
+      sm_ml[(wave * kMaxRows + n16) * 2 + 1] = l_run;
     }
   }
   __syncthreads();
 
-  for (int o = tid; o < g * kHeadDim; o += 256) {
+  for (int o = tid; o < rows * kHeadDim; o += 256) {
     const int h = o / kHeadDim, dd = o % kHeadDim;
     float ma = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) ma = fmaxf(ma, sm_ml[(w * kMaxGroup + h) * 2]);
+    for (int w = 0; w < 4; ++w) ma = fmaxf(ma, sm_ml[(w * kMaxRows + h) * 2]);
     float ls = 0.f, a = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float mw = sm_ml[(w * kMaxGroup + h) * 2];
+      const float mw = sm_ml[(w * kMaxRows + h) * 2];
       const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - ma);
-      ls += sm_ml[(w * kMaxGroup + h) * 2 + 1] * f;
-      a += sm_acc[(w * kMaxGroup + h) * kHeadDim + dd] * f;
+      ls += sm_ml[(w * kMaxRows + h) * 2 + 1] * f;
+      a += sm_acc[(w * kMaxRows + h) * kHeadDim + dd] * f;
     }
     emit_slice(p, i, hk, split, h, dd, ma, ls, a);
   }

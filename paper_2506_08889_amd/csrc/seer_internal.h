@@ -7,9 +7,10 @@ namespace seer {
 
 constexpr int kHeadDim = 128;   // d and d_gate; one row is 256 bytes = 16 lanes x 16 B
 constexpr int kMaxGroup = 8;    // query heads per kv head
+constexpr int kMaxRows = 16;    // query rows (new tokens x heads of a group) per kv head = one MFMA tile side
 
 struct DecodeParams {
-  const uint16_t* q;            // bf16 [B,Hq,128]
+  const uint16_t* q;            // bf16 [B,q_len,Hq,128]
   const uint16_t* k;
   const uint16_t* v;
   int64_t stride_seq, stride_head, stride_token;
@@ -20,12 +21,13 @@ struct DecodeParams {
   const int32_t* nblk;          // [B,Hkv]
   int32_t max_blocks;           // max_sel (sparse) or block cap (dense)
   int32_t B, Hq, Hkv, g, block_size;
+  int32_t q_len, rows;          // new tokens per sequence (1 = plain decode), rows = q_len * g
   float scale_log2e;            // scale * log2(e): logits are kept in the base-2 domain
   int32_t num_splits, blocks_per_split;
-  float* part_acc;              // [B*Hkv, num_splits, g, 128] unnormalised partial outputs
-  float* part_ml;               // [B*Hkv, num_splits, g, 2]   running max (base-2 domain), sum
-  void* out;                    // [B,Hq,128] bf16 or fp32
-  float* lse;                   // [B,Hq] or nullptr
+  float* part_acc;              // [B*Hkv, num_splits, rows, 128] unnormalised partial outputs
+  float* part_ml;               // [B*Hkv, num_splits, rows, 2]   running max (base-2 domain), sum
+  void* out;                    // [B,q_len,Hq,128] bf16 or fp32
+  float* lse;                   // [B,q_len,Hq] or nullptr
   int32_t out_is_f32;
 };
 
@@ -161,15 +163,21 @@ __device__ __forceinline__ void store_output(const DecodeParams& p, int64_t row,
   if (dd == 0 && p.lse) p.lse[row] = (l > 0.f) ? (ma + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
-// What a split kernel does with the merged (ma, l, a) of its slice for (head h, feature dd):
+// Row r of a group's tile is (new token t = r / g, head h = r % g); its place in out / lse.
+__device__ __forceinline__ int64_t output_row(const DecodeParams& p, int i, int hk, int r) {
+  const int t = r / p.g, h = r - t * p.g;
+  return ((int64_t)i * p.q_len + t) * p.Hq + (int64_t)hk * p.g + h;
+}
+
+// What a split kernel does with the merged (ma, l, a) of its slice for (row r, feature dd):
 // with a single split it is the final result, otherwise a partial for the merge kernel.
-__device__ __forceinline__ void emit_slice(const DecodeParams& p, int i, int hk, int split, int h,
+__device__ __forceinline__ void emit_slice(const DecodeParams& p, int i, int hk, int split, int r,
                                            int dd, float ma, float l, float a) {
   const int64_t grp = (int64_t)i * p.Hkv + hk;
   if (p.num_splits == 1) {
-    store_output(p, (int64_t)i * p.Hq + (int64_t)hk * p.g + h, dd, ma, l, a);
+    store_output(p, output_row(p, i, hk, r), dd, ma, l, a);
   } else {
-    const int64_t pidx = (grp * p.num_splits + split) * p.g + h;
+    const int64_t pidx = (grp * p.num_splits + split) * p.rows + r;
     p.part_acc[pidx * kHeadDim + dd] = a;
     if (dd == 0) {
       p.part_ml[pidx * 2 + 0] = ma;
@@ -182,8 +190,8 @@ __device__ __forceinline__ void emit_slice(const DecodeParams& p, int i, int hk,
 // single split it owns the (empty) result of the group.
 __device__ __forceinline__ void emit_empty_if_single_split(const DecodeParams& p, int i, int hk) {
   if (p.num_splits != 1) return;
-  for (int o = threadIdx.x; o < p.g * kHeadDim; o += blockDim.x)
-    store_output(p, (int64_t)i * p.Hq + (int64_t)hk * p.g + o / kHeadDim, o % kHeadDim, -INFINITY, 0.f, 0.f);
+  for (int o = threadIdx.x; o < p.rows * kHeadDim; o += blockDim.x)
+    store_output(p, output_row(p, i, hk, o / kHeadDim), o % kHeadDim, -INFINITY, 0.f, 0.f);
 }
 
 }  // namespace seer

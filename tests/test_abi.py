@@ -50,7 +50,7 @@ def test_workspace_queries():
         seer.decode_workspace_bytes(1, 8, 2, 64, 16)        # head dim 64 is not built
     assert e.value.status == -3
     with pytest.raises(seer.SeerError) as e:
-        seer.decode_workspace_bytes(1, 18, 2, 128, 16)      # group of 9 heads
+        seer.decode_workspace_bytes(1, 34, 2, 128, 16)      # 17 query rows per kv head (16 = tokens x heads is the cap)
     assert e.value.status == -3
     with pytest.raises(seer.SeerError):
         seer.gate_workspace_bytes(0, 8, 16)

@@ -510,3 +510,42 @@ def test_randomised_shapes_gate_and_decode():
                                      page_table=inp.page_table, page_size=inp.page_size, out_dtype=torch.float32)
         torch.cuda.synchronize()
         check_decode(out, lse, dref_out, dref_lse, tight=True, what=f"rand {case} dense")
+
+
+@pytest.mark.parametrize("g,T,bs", [(4, 4, 64), (5, 3, 64), (2, 8, 128), (8, 2, 32), (4, 1, 64), (1, 16, 64)])
+def test_multi_token_decode(g, T, bs):
+    """q_len new tokens per sequence in one call: each query against the oracle (causal among the
+    new tokens, shared block list), for several split plans; sequences shorter than q_len included."""
+    Hkv = 2
+    S = (bs * 9 + 5, bs * 4, T - 1 if T > 1 else 1, bs * 6 + bs // 2 + 1)
+    w = synth.Workload("mtp", B=4, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen=max(S), budget_tokens=bs * 4, seed=500 + g * T)
+    inp = synth.make_inputs(w, "cpu")
+    inp.seqlens_cpu = torch.tensor(S, dtype=torch.int32)
+    inp.seqlens = inp.seqlens_cpu.clone()
+    inp = to_dev(inp)
+    gen = torch.Generator().manual_seed(g * 100 + T)
+    qm = torch.randn(4, T, g * Hkv, 128, generator=gen).to(torch.bfloat16)
+    nb = (inp.seqlens_cpu + bs - 1) // bs
+    idx, cnt = synth.random_block_lists(4, Hkv, nb, [6, 3, 1, 5], 6, gen, ascending=False)
+    for i in range(4):           # the last block (where the causal limits bite) is always listed
+        if int(nb[i]) > 0 and (idx[i, 0, :int(cnt[i, 0])] == int(nb[i]) - 1).sum() == 0:
+            idx[i, :, 0] = int(nb[i]) - 1
+    ref_out, ref_lse = oracle.sparse_decode_multi(qm, oracle.KVLayout(cpu(inp.k), cpu(inp.v)), inp.seqlens_cpu, idx, cnt,
+                                                  bs, w.scale)
+    for ns in (0, 1, 3):
+        seer.set_knob(1, ns)
+        out, lse = seer.sparse_decode_multi(qm.to(DEV), inp.k, inp.v, inp.seqlens, idx.to(DEV), cnt.to(DEV), bs, w.scale,
+                                            out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        check_decode(out.view(4, T * g * Hkv, 128), lse.view(4, T * g * Hkv), ref_out.reshape(4, T * g * Hkv, 128),
+                     ref_lse.reshape(4, T * g * Hkv), tight=True, what=f"multi-token g={g} T={T} bs={bs} ns={ns}")
+    if T == 1:                   # one new token is the plain call
+        o1, l1 = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+        o1 = o1.clone(); inp.q = qm[:, 0].contiguous().to(DEV)
+        o2, l2 = gpu_decode(inp, idx.to(DEV), cnt.to(DEV), torch.float32)
+        assert torch.equal(o2, out[:, 0]) and torch.equal(l2, lse[:, 0])
+    # too many rows for the tile / unsupported block size are refused, not mis-computed
+    if g * T == 16:
+        with pytest.raises(seer.SeerError):
+            seer.sparse_decode_multi(torch.zeros(4, T + 1, g * Hkv, 128, dtype=torch.bfloat16, device=DEV), inp.k, inp.v,
+                                     inp.seqlens, idx.to(DEV), cnt.to(DEV), bs, w.scale)

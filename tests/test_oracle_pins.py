@@ -478,3 +478,36 @@ def test_top_p_mode_matches_sorted_cumulative_probabilities():
     idx, cnt = oracle.gate_select(qg, kc8, torch.tensor([8 * b, 8 * b], dtype=torch.int32), b, mode=oracle.SELECT_TOPP,
                                   threshold=0.5, max_sel=8)
     assert (cnt == 4).all() and idx[0, 0, :4].tolist() == [0, 1, 2, 3]
+
+
+def test_multi_token_decode_is_a_stack_of_single_token_decodes_and_causal():
+    """Query t of T new tokens == single-token decode of the sequence cut at that token (same list);
+    and independently: dense causal attention over the last T positions when every block is listed."""
+    q, k, v, sl = rand_case(17, B=2, S=(300, 135))
+    T = 3
+    g = torch.Generator().manual_seed(3)
+    qm = torch.randn(2, T, 8, 128, generator=g).to(torch.bfloat16)
+    idx = np.array([[[0, 2, 4, -1, -1], [1, 3, 4, -1, -1]], [[0, 1, 2, -1, -1], [2, 0, -1, -1, -1]]], dtype=np.int32)
+    cnt = np.array([[3, 3], [3, 2]], dtype=np.int32)
+    out, lse = oracle.sparse_decode_multi(qm, KVLayout(k, v), sl, idx, cnt, 64, SCALE)
+    for t in range(T):
+        cut = sl - (T - 1 - t)
+        o1, l1 = oracle.sparse_decode(qm[:, t].contiguous(), KVLayout(k, v), cut, idx, cnt, 64, SCALE)
+        np.testing.assert_allclose(out[:, t], o1, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse[:, t], l1, rtol=0, atol=1e-12)
+    # all blocks listed: textbook causal attention of the last T tokens (independent numpy)
+    idx_all, cnt_all = all_blocks(2, 2, sl, 64, 5)
+    out, lse = oracle.sparse_decode_multi(qm, KVLayout(k, v), sl, idx_all, cnt_all, 64, SCALE)
+    for t in range(T):
+        ro, rl = dense_reference(qm[:, t], k, v, sl - (T - 1 - t), SCALE)
+        np.testing.assert_allclose(out[:, t], ro, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse[:, t], rl, rtol=0, atol=1e-12)
+    # a later token never leaks into an earlier query: changing the last key/value leaves queries 0..T-2 alone
+    k2, v2 = k.clone(), v.clone()
+    k2[0, :, 299] = 3.0; v2[0, :, 299] = -5.0
+    out2, _ = oracle.sparse_decode_multi(qm, KVLayout(k2, v2), sl, idx_all, cnt_all, 64, SCALE)
+    np.testing.assert_array_equal(out2[0, :T - 1], out[0, :T - 1])
+    assert np.abs(out2[0, T - 1] - out[0, T - 1]).max() > 1e-3
+    # more new tokens than the sequence holds: the earliest queries see nothing
+    out3, lse3 = oracle.sparse_decode_multi(qm, KVLayout(k, v), torch.tensor([2, 1], dtype=torch.int32), idx_all, cnt_all, 64, SCALE)
+    assert np.isneginf(lse3[0, 0]).all() and np.isfinite(lse3[0, 1]).all() and np.isneginf(lse3[1, :2]).all()
