@@ -246,6 +246,34 @@ def run_workload(args, workload, seer, synth, torch, np, full):
                     "ms_per_step_with_gate_q": ms_step + ms_q}
         del wq, wk, rcos, rsin, kc_out
 
+    # ---- several new tokens per call (multi-token / speculative decoding): same bytes, q_len x the tokens
+    multi = None
+    if full and 16 // w.g >= 2 and bs % 32 == 0:
+        T = min(16 // w.g, 4)
+        qm = synth.randn_bf16((B, T, Hq, d), dev, synth.generator(dev, w.seed + 3000))
+        out_m = torch.empty(B, T, Hq, d, dtype=torch.bfloat16, device=dev)
+        lse_m = torch.empty(B, T, Hq, dtype=torch.float32, device=dev)
+        ws_m = torch.empty(seer.decode_workspace_bytes(B, Hq * T, Hkv, d, max_sel), dtype=torch.uint8, device=dev)
+
+        def mt(i):
+            k_, v_ = caches[i % kv_copies]
+            seer.sparse_decode_multi(qm, k_, v_, base.seqlens, idxs[i % R], cnts[i % R], bs, w.scale,
+                                     page_table=base.page_table, page_size=base.page_size, out=out_m, lse=lse_m,
+                                     workspace=ws_m)
+
+        for i in range(3):
+            mt(i)
+        seer.profile_reset()
+        seer.profile_enable(True)
+        ms_mt = timed(mt, 10)
+        seer.profile_enable(False)
+        n_m, t_m = seer.profile_read(2)
+        seer.profile_reset()
+        mt_us = t_m / n_m * 1e3
+        multi = {"q_len": T, "query_rows_per_kv_head": T * w.g, "split_kernel_us": mt_us, "ms_per_call": ms_mt,
+                 "decode_tokens_per_s": B * T / (ms_mt * 1e-3)}
+        del qm, out_m, lse_m, ws_m
+
     if args.calibrate_copy_mib > 0:
         a = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         b_ = torch.empty_like(a)
@@ -297,6 +325,7 @@ def run_workload(args, workload, seer, synth, torch, np, full):
         "gate_GBps": ab["gate"] / (((kern["gate_score"]["avg_us"] or 0.0) + (kern["gate_select"]["avg_us"] or 0.0)) * 1e-6) / 1e9,
         "stream_read_GBps": stream_gbps,
         "frontend": frontend,
+        "multi_token_decode": multi,
         "dense": None, "speedup_vs_dense": None,
         "paper_context": "paper: up to 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware, not a target)",
     }
