@@ -84,6 +84,7 @@ def main():
     seer.load_library()
     result = run_workload(args, args.workload, seer, synth, torch, np, full=True)
     if args.also and args.also != args.workload:
+        time.sleep(3)      # let the GPU settle after the dense runs of the main workload
         sec = run_workload(args, args.also, seer, synth, torch, np, full=False)
         result["also"] = {args.also: {k: sec[k] for k in ("value", "unit", "ms_per_step", "config", "roofline",
                                                            "kernels_avg_us", "dense", "speedup_vs_dense")}}

@@ -164,9 +164,8 @@ def gate_select(q_gate: torch.Tensor, kc_cache: torch.Tensor, seqlens: torch.Ten
     _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk")
     if budget_blocks is not None:
         _want(budget_blocks, torch.int32, "budget_blocks")
-    need = gate_workspace_bytes(B, Hkv, nb_max)
     if workspace is None:
-        workspace = _workspace(need, dev)
+        workspace = _workspace(gate_workspace_bytes(B, Hkv, nb_max), dev)
     st = lib.seer_gate_select(_ptr(q_gate), _ptr(kc_cache), kc_cache.stride(0), kc_cache.stride(1),
                               kc_cache.stride(2), _ptr(seqlens), B, Hkv, Dg, nb_max, block_size, mode,
                               int(budget_tokens), _ptr(budget_blocks), float(threshold), _ptr(block_idx),
@@ -227,9 +226,8 @@ def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: to
     max_sel = block_idx.shape[2]
     lay = _layout(k, v, page_table, page_size)
     out, lse = _decode_out(q, out, lse, out_dtype)
-    need = decode_workspace_bytes(B, Hq, Hkv, d, max_sel)
     if workspace is None:
-        workspace = _workspace(need, q.device)
+        workspace = _workspace(decode_workspace_bytes(B, Hq, Hkv, d, max_sel), q.device)
     st = lib.seer_sparse_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
                                 max_sel, B, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
                                 0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
@@ -281,9 +279,8 @@ def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: tor
     Hkv = k.shape[1]
     lay = _layout(k, v, page_table, page_size)
     out, lse = _decode_out(q, out, lse, out_dtype)
-    need = decode_workspace_bytes(B, Hq, Hkv, d, max_blocks)
     if workspace is None:
-        workspace = _workspace(need, q.device)
+        workspace = _workspace(decode_workspace_bytes(B, Hq, Hkv, d, max_blocks), q.device)
     st = lib.seer_dense_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), max_blocks, B, Hq, Hkv, d,
                                block_size, ctypes.c_float(scale), _ptr(out),
                                0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
