@@ -1,0 +1,103 @@
+/*
+ * Pure-C user of the library: no Python, no torch.  Allocates with the HIP runtime, runs one tiny
+ * gate-selection + sparse-decode step through the C ABI of include/seer.h and checks it against the
+ * CPU oracle (oracle/seer_oracle.c, linked in as the checker).  Exit code 0 = parity.
+ *
+ * Workload: batch 2, 8 query / 2 kv heads, head dim 128, block 64, sequence lengths 1000 and 333
+ * (both end in a partial block), token budget 512; inputs from a fixed linear congruential generator.
+ */
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/seer.h"
+
+/* oracle entry points (see oracle/seer_oracle.c) */
+typedef struct {
+  const uint16_t* k; const uint16_t* v;
+  int64_t stride_seq, stride_head, stride_token;
+  const int32_t* page_table; int32_t max_pages, page_size;
+} oracle_kv_t;
+int oracle_gate_select(const uint16_t*, const uint16_t*, int64_t, int64_t, int64_t, const int32_t*, int, int, int, int,
+                       int, int, int32_t, const int32_t*, double, int32_t*, int32_t*, int, double*);
+int oracle_sparse_decode(const uint16_t*, const oracle_kv_t*, const int32_t*, const int32_t*, const int32_t*, int, int,
+                         int, int, int, int, float, double*, double*, const uint8_t*);
+
+#define CHECK_HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "HIP error %d at %s:%d\n", (int)e_, __FILE__, __LINE__); return 2; } } while (0)
+#define CHECK_SEER(x) do { seer_status s_ = (x); if (s_ != SEER_OK) { fprintf(stderr, "%s -> %s\n", #x, seer_status_string(s_)); return 3; } } while (0)
+
+static uint32_t lcg_state = 12345u;
+static float uniform_pm1(void) {             /* uniform in (-1, 1) */
+  lcg_state = lcg_state * 1664525u + 1013904223u;
+  return ((lcg_state >> 8) / 8388608.0f) - 1.0f;
+}
+static uint16_t to_bf16(float f) {           /* round to nearest even */
+  uint32_t u; memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+static float from_bf16(uint16_t h) { uint32_t u = (uint32_t)h << 16; float f; memcpy(&f, &u, 4); return f; }
+static void fill(uint16_t* p, size_t n, float scale) { for (size_t i = 0; i < n; ++i) p[i] = to_bf16(scale * 1.7f * uniform_pm1()); }
+
+int main(void) {
+  enum { B = 2, Hq = 8, Hkv = 2, D = 128, BS = 64, SMAX = 1024, NB = SMAX / BS, BUDGET = 512, MAXSEL = BUDGET / BS };
+  const int32_t seqlens[B] = {1000, 333};
+  const float scale = 1.0f / sqrtf((float)D);
+  const size_t nq = (size_t)B * Hq * D, nkv = (size_t)B * Hkv * SMAX * D, nqg = (size_t)B * Hkv * D, nkc = (size_t)B * Hkv * NB * D;
+  uint16_t *q = malloc(nq * 2), *k = malloc(nkv * 2), *v = malloc(nkv * 2), *qg = malloc(nqg * 2), *kc = malloc(nkc * 2);
+  fill(q, nq, 1.f); fill(k, nkv, 1.f); fill(v, nkv, 1.f); fill(qg, nqg, 1.f); fill(kc, nkc, 1.f);
+
+  /* ---- oracle ---- */
+  int32_t ref_idx[B * Hkv * MAXSEL], ref_cnt[B * Hkv];
+  if (oracle_gate_select(qg, kc, (int64_t)Hkv * NB * D, (int64_t)NB * D, D, seqlens, B, Hkv, D, NB, BS, 0, BUDGET, NULL, 0.0,
+                         ref_idx, ref_cnt, MAXSEL, NULL)) return 4;
+  oracle_kv_t okv = {k, v, (int64_t)Hkv * SMAX * D, (int64_t)SMAX * D, D, NULL, 0, 0};
+  double* ref_out = malloc(nq * sizeof(double));
+  double ref_lse[B * Hq];
+  if (oracle_sparse_decode(q, &okv, seqlens, ref_idx, ref_cnt, MAXSEL, B, Hq, Hkv, D, BS, scale, ref_out, ref_lse, NULL)) return 4;
+
+  /* ---- device ---- */
+  void *dq, *dk, *dv, *dqg, *dkc, *dsl, *didx, *dcnt, *dout, *dlse, *ws_g, *ws_d;
+  size_t wsg = 0, wsd = 0;
+  CHECK_SEER(seer_gate_workspace_bytes(B, Hkv, NB, &wsg));
+  CHECK_SEER(seer_decode_workspace_bytes(B, Hq, Hkv, D, MAXSEL, &wsd));
+  CHECK_HIP(hipMalloc(&dq, nq * 2)); CHECK_HIP(hipMalloc(&dk, nkv * 2)); CHECK_HIP(hipMalloc(&dv, nkv * 2));
+  CHECK_HIP(hipMalloc(&dqg, nqg * 2)); CHECK_HIP(hipMalloc(&dkc, nkc * 2)); CHECK_HIP(hipMalloc(&dsl, sizeof seqlens));
+  CHECK_HIP(hipMalloc(&didx, sizeof ref_idx)); CHECK_HIP(hipMalloc(&dcnt, sizeof ref_cnt));
+  CHECK_HIP(hipMalloc(&dout, nq * 4)); CHECK_HIP(hipMalloc(&dlse, B * Hq * 4));
+  CHECK_HIP(hipMalloc(&ws_g, wsg)); CHECK_HIP(hipMalloc(&ws_d, wsd));
+  CHECK_HIP(hipMemcpy(dq, q, nq * 2, hipMemcpyHostToDevice)); CHECK_HIP(hipMemcpy(dk, k, nkv * 2, hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemcpy(dv, v, nkv * 2, hipMemcpyHostToDevice)); CHECK_HIP(hipMemcpy(dqg, qg, nqg * 2, hipMemcpyHostToDevice));
+  CHECK_HIP(hipMemcpy(dkc, kc, nkc * 2, hipMemcpyHostToDevice)); CHECK_HIP(hipMemcpy(dsl, seqlens, sizeof seqlens, hipMemcpyHostToDevice));
+  hipStream_t stream;
+  CHECK_HIP(hipStreamCreate(&stream));
+
+  CHECK_SEER(seer_gate_select(dqg, dkc, (int64_t)Hkv * NB * D, (int64_t)NB * D, D, dsl, B, Hkv, D, NB, BS, SEER_SELECT_TOPK,
+                              BUDGET, NULL, 0.0, didx, dcnt, MAXSEL, ws_g, wsg, stream));
+  seer_kv_layout kv = {dk, dv, (int64_t)Hkv * SMAX * D, (int64_t)SMAX * D, D, NULL, 0, 0};
+  CHECK_SEER(seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, stream));
+  CHECK_HIP(hipStreamSynchronize(stream));
+
+  int32_t idx[B * Hkv * MAXSEL], cnt[B * Hkv];
+  float* out = malloc(nq * 4);
+  float lse[B * Hq];
+  CHECK_HIP(hipMemcpy(idx, didx, sizeof idx, hipMemcpyDeviceToHost)); CHECK_HIP(hipMemcpy(cnt, dcnt, sizeof cnt, hipMemcpyDeviceToHost));
+  CHECK_HIP(hipMemcpy(out, dout, nq * 4, hipMemcpyDeviceToHost)); CHECK_HIP(hipMemcpy(lse, dlse, sizeof lse, hipMemcpyDeviceToHost));
+
+  if (memcmp(idx, ref_idx, sizeof idx) || memcmp(cnt, ref_cnt, sizeof cnt)) { fprintf(stderr, "block indices differ from the oracle\n"); return 5; }
+  double max_err = 0.0, max_lse = 0.0;
+  for (size_t i = 0; i < nq; ++i) { double e = fabs((double)out[i] - ref_out[i]); if (e > max_err) max_err = e; }
+  for (int i = 0; i < B * Hq; ++i) { double e = fabs((double)lse[i] - ref_lse[i]); if (e > max_lse) max_lse = e; }
+  printf("c_abi_check: indices bit-exact (%d + %d blocks), max |out - oracle| = %.3e, max |lse - oracle| = %.3e\n",
+         cnt[0], cnt[Hkv], max_err, max_lse);
+  (void)from_bf16;
+  if (!(max_err <= 2e-4) || !(max_lse <= 1e-4)) { fprintf(stderr, "outside tolerance\n"); return 6; }
+
+  /* error paths need no device work */
+  if (seer_sparse_decode(NULL, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, stream) != SEER_ERR_NULL) return 7;
+  if (seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, 16, stream) != SEER_ERR_WORKSPACE) return 7;
+  return 0;
+}

@@ -549,3 +549,18 @@ def test_multi_token_decode(g, T, bs):
         with pytest.raises(seer.SeerError):
             seer.sparse_decode_multi(torch.zeros(4, T + 1, g * Hkv, 128, dtype=torch.bfloat16, device=DEV), inp.k, inp.v,
                                      inp.seqlens, idx.to(DEV), cnt.to(DEV), bs, w.scale)
+
+
+def test_pure_c_program_through_the_abi():
+    """tests/c_abi/c_abi_check.c uses the library from plain C (HIP runtime allocations, no torch)
+    and compares with the C oracle itself; built by __graft_entry__.build()."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "c_abi_check")
+    if not os.path.exists(exe):
+        import __graft_entry__
+        __graft_entry__.build_c_abi_check()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(r.stdout, r.stderr)
+    assert r.returncode == 0, f"c_abi_check failed with {r.returncode}: {r.stderr}"
+    assert "indices bit-exact" in r.stdout
