@@ -564,3 +564,32 @@ def test_pure_c_program_through_the_abi():
     print(r.stdout, r.stderr)
     assert r.returncode == 0, f"c_abi_check failed with {r.returncode}: {r.stderr}"
     assert "indices bit-exact" in r.stdout
+
+
+def test_gate_very_long_cache_and_crowded_boundary():
+    """(a) A compression cache longer than the select kernel keeps in LDS (> 8192 blocks): scores are
+    re-read from global memory and only the radix walk is available.  (b) A boundary bin holding more
+    equal scores than the fast path ranks exactly: it must fall back, ties still lowest index first."""
+    gen = torch.Generator().manual_seed(91)
+    B, Hkv, nb_max, bs = 1, 2, 8300, 16
+    qg = torch.randn(B, Hkv, 128, generator=gen).to(torch.bfloat16)
+    kc = torch.randn(B, Hkv, nb_max, 128, generator=gen).to(torch.bfloat16)
+    sl = torch.tensor([nb_max * bs - 3], dtype=torch.int32)          # last block partial
+    for mode, kw in ((seer.SELECT_TOPK, dict(budget_tokens=700 * bs, max_sel=700)),
+                     (seer.SELECT_THRESHOLD, dict(threshold=2.0e-4, max_sel=nb_max)),
+                     (seer.SELECT_TOPP, dict(threshold=0.6, max_sel=nb_max))):
+        ri, rc = oracle.gate_select(qg, kc, sl, bs, mode=mode, **kw)
+        gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, mode=mode, **kw)
+        torch.cuda.synchronize()
+        check_indices(gi, gc, ri, rc, what=f"8300-block cache mode={mode}")
+    # (b) 900 of 1000 blocks share one score, the k-th largest falls among them
+    nb2 = 1000
+    kc2 = torch.randn(1, 2, nb2, 128, generator=gen).to(torch.bfloat16)
+    same = torch.randperm(nb2, generator=gen)[:900]
+    kc2[0, :, same] = kc2[0, :, same[0]].unsqueeze(1)
+    sl2 = torch.tensor([nb2 * 64], dtype=torch.int32)
+    for budget_blocks in (30, 400, 950):
+        ri, rc = oracle.gate_select(qg, kc2, sl2, 64, budget_tokens=budget_blocks * 64, max_sel=budget_blocks)
+        gi, gc = gate_both_impls(qg.to(DEV), kc2.to(DEV), sl2.to(DEV), 64, budget_tokens=budget_blocks * 64,
+                                 max_sel=budget_blocks)
+        check_indices(gi, gc, ri, rc, what=f"crowded boundary k={budget_blocks}")
