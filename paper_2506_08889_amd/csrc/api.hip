@@ -41,8 +41,11 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // How the block list is cut: num_splits slices of blocks_per_split list entries each (the
 // partition runs over the list capacity, not over the blocks of the sequence, Sec. 3.3).
-// The split kernels keep 2 work-groups per CU resident.  For lists of equal length one resident
-// round of work-groups is best (measured on MI355X), with at least 4 list entries per slice.
+// Measured on MI355X for lists of equal length: about one work-group per CU is enough to reach
+// the HBM rate, more slices only add partials for the merge kernel; and a merge launch costs
+// about 6.5 us, which a work-group needs to read about 8 blocks of 64 tokens by itself
+// (~0.8 us each), so short lists are only cut when the slices save more than the merge costs.
+// A slice has at least 4 list entries.
 // Lists of very different lengths (SEER_KNOB_DECODE_RAGGED) get slices of about 2048 tokens so
 // that the longest list is spread over many work-groups; equal-length lists lose ~5 % to that,
 // hence the opt-in.
@@ -56,12 +59,19 @@ long max_splits_for(int max_blocks) {
 
 void plan_splits(int B, int Hkv, int max_blocks, int block_size, int* num_splits, int* blocks_per_split) {
   const long groups = (long)B * Hkv;
-  const long slots = (long)cu_count() * 2;
+  const long slots = (long)cu_count();
+  const long cap = max_splits_for(max_blocks);
   long ns;
   if (g_knob_splits > 0) {
     ns = g_knob_splits;
   } else {
     ns = groups >= slots ? 1 : (slots + groups / 2) / groups;
+    if (ns > cap) ns = cap;
+    if (ns > 1) {
+      // microseconds a lone work-group saves by reading max_blocks / ns blocks instead of all
+      const double saved = 0.8 * (block_size / 64.0) * max_blocks * (1.0 - 1.0 / (double)ns);
+      if (saved < 6.5) ns = 1;
+    }
     if (g_knob_ragged) {
       long len_r = 2048 / block_size;
       if (len_r < kMinSliceBlocks) len_r = kMinSliceBlocks;
@@ -69,7 +79,6 @@ void plan_splits(int B, int Hkv, int max_blocks, int block_size, int* num_splits
       if (ns_r > ns) ns = ns_r;
     }
   }
-  const long cap = max_splits_for(max_blocks);
   if (ns > cap) ns = cap;
   if (ns < 1) ns = 1;
   long len = (max_blocks + ns - 1) / ns;
