@@ -82,6 +82,9 @@ def _load():
         lib.oracle_kc_update.argtypes = [ctypes.POINTER(_KV), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p] + \
             [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_attn_ground_truth.restype = ctypes.c_int
+        lib.oracle_attn_ground_truth.argtypes = [ctypes.c_void_p, ctypes.POINTER(_KV), ctypes.c_void_p] + \
+            [ctypes.c_int] * 6 + [ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -301,3 +304,29 @@ def sparse_decode_multi(q, kv: KVLayout, seqlens, block_idx, nblk, block_size: i
     if rc != 0:
         raise ValueError("oracle_sparse_decode_multi: bad sizes")
     return out, lse
+
+
+def attn_ground_truth(q, k, v, block_size: int, scale: float, seqlens=None):
+    """Training-side ground truth of the AttnGate (Sec. 2.3) together with the dense causal
+    attention it is pooled from.  q [B,T,Hq,d] bf16; k, v [B,Hkv,T,d] bf16 views (any strides on the
+    first three dims); seqlens [B] or None.  Returns (out [B,T,Hq,d], lse [B,T,Hq],
+    gt [B,Hkv,T,ceil(T/block_size)]) as fp64 arrays; every gt row of a real query sums to 1."""
+    lib = _load()
+    qb = np.ascontiguousarray(_bits(q))
+    B, T, Hq, d = qb.shape
+    kb, vb = _bits(k), _bits(v)
+    assert kb.shape == vb.shape and kb.strides == vb.strides and kb.shape[0] == B and kb.shape[3] == d
+    assert kb.shape[2] >= T
+    Hkv = kb.shape[1]
+    st, _, _ = _kv_struct(k, None, 0, B)
+    st.v = vb.ctypes.data
+    sl = _i32(seqlens)
+    nb = (T + block_size - 1) // block_size
+    out = np.full((B, T, Hq, d), np.nan, dtype=np.float64)
+    lse = np.full((B, T, Hq), np.nan, dtype=np.float64)
+    gt = np.full((B, Hkv, T, nb), np.nan, dtype=np.float64)
+    rc = lib.oracle_attn_ground_truth(_ptr(qb), ctypes.byref(st), _ptr(sl), B, T, Hq, Hkv, d, block_size,
+                                      ctypes.c_float(scale), _ptr(out), _ptr(lse), _ptr(gt))
+    if rc != 0:
+        raise ValueError("oracle_attn_ground_truth: bad sizes")
+    return out, lse, gt

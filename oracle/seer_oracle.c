@@ -23,10 +23,19 @@
  * No blocking, no online rescaling, no split-K: two passes over the selected
  * tokens (max, then sums), sums taken in index order.
  *
+ *   ground truth    (training side, Sec. 2.3) causal softmax attention of every query
+ *                   position; per query row the probabilities are max-pooled over the
+ *                   keys of each block (column-wise 1-D pooling), then over the query
+ *                   heads that share a kv head, then divided by their sum over blocks
+ *
  * Pins (tests/test_oracle_pins.py): dense attention computed independently when all
  * blocks are selected; closed forms for identical keys; needle keys; -inf masking
  * equivalence; lse partition algebra; brute-force subset enumeration for the top-k;
  * exact rational arithmetic for the score; softmax invariants for the threshold.
+ * Ground truth (tests/test_oracle_gt_pins.py): zero queries (uniform rows: prefix means and
+ * 1 / #visible-blocks in closed form); needle keys (one-hot rows); agreement of out / lse with
+ * the decode oracle run per position; a grouped call equals the normalised head-wise maximum of
+ * single-head calls; sum-to-one, causality and permutation properties.
  */
 #include <math.h>
 #include <stdint.h>
@@ -481,6 +490,79 @@ int oracle_sparse_decode_multi(const uint16_t* q, const oracle_kv_t* kv, const i
           for (int c = 0; c < d; ++c) orow[c] /= Z;
           lse[row] = m + log(Z);
         }
+      }
+    }
+  }
+  return 0;
+}
+
+/* ------------------------------------------------ distillation ground truth (Sec. 2.3) */
+
+/*
+ * Dense causal attention over whole sequences plus the AttnGate's training target.
+ * q [B,T,Hq,d] bf16; keys / values addressed through kv (token s of sequence i, kv head hk);
+ * seqlens [B] or NULL (all T): query rows t >= S_i are padding (out = 0, lse = -inf, gt = 0).
+ * For query t < S_i and head h (kv head hk = h / g):
+ *     x_s = scale * q.k_s, s = 0..t;   P_s = exp(x_s - lse),  lse = log sum_s exp(x_s)
+ *     out = sum_s P_s v_s
+ *     c[h][j] = max of P_s over the keys s <= t of block j          (1-D column pooling)
+ *     r[hk][j] = max of c[h][j] over the g heads of kv head hk      (pooling inside the GQA group)
+ *     gt[hk][j] = r[hk][j] / sum_j' r[hk][j']                       (normalised to sum 1)
+ * Blocks that start after t hold no visible key: gt = 0 there.
+ * out [B,T,Hq,d], lse [B,T,Hq], gt [B,Hkv,T,nb] with nb = ceil(T / block_size); all fp64.
+ */
+int oracle_attn_ground_truth(const uint16_t* q, const oracle_kv_t* kv, const int32_t* seqlens, int B, int T,
+                             int Hq, int Hkv, int d, int block_size, float scale, double* out, double* lse,
+                             double* gt) {
+  if (Hkv <= 0 || Hq % Hkv || T <= 0 || block_size <= 0) return -1;
+  const int g = Hq / Hkv;
+  const int nb = (T + block_size - 1) / block_size;
+#pragma omp parallel for collapse(3) schedule(dynamic)
+  for (int i = 0; i < B; ++i) {
+    for (int hk = 0; hk < Hkv; ++hk) {
+      for (int t = 0; t < T; ++t) {
+        int S = seqlens ? seqlens[i] : T;
+        if (S > T) S = T;
+        double* grow = gt + (((int64_t)i * Hkv + hk) * T + t) * nb;
+        for (int j = 0; j < nb; ++j) grow[j] = 0.0;
+        if (t >= S) {
+          for (int hh = 0; hh < g; ++hh) {
+            const int64_t row = ((int64_t)i * T + t) * Hq + hk * g + hh;
+            for (int c = 0; c < d; ++c) out[row * d + c] = 0.0;
+            lse[row] = -INFINITY;
+          }
+          continue;
+        }
+        double* x = (double*)malloc(sizeof(double) * (size_t)(t + 1));
+        for (int hh = 0; hh < g; ++hh) {
+          const int64_t row = ((int64_t)i * T + t) * Hq + hk * g + hh;
+          const uint16_t* qrow = q + row * d;
+          double m = -INFINITY;
+          for (int s = 0; s <= t; ++s) {
+            const uint16_t* krow = kv->k + token_offset(kv, i, hk, s);
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += bf16_value(qrow[c]) * bf16_value(krow[c]);
+            x[s] = (double)scale * dot;
+            if (x[s] > m) m = x[s];
+          }
+          double Z = 0.0;
+          for (int s = 0; s <= t; ++s) Z += exp(x[s] - m);
+          const double l = m + log(Z);
+          double* orow = out + row * d;
+          for (int c = 0; c < d; ++c) orow[c] = 0.0;
+          for (int s = 0; s <= t; ++s) {
+            const double p = exp(x[s] - l);
+            const uint16_t* vrow = kv->v + token_offset(kv, i, hk, s);
+            for (int c = 0; c < d; ++c) orow[c] += p * bf16_value(vrow[c]);
+            const int j = s / block_size;
+            if (p > grow[j]) grow[j] = p;          /* max over the block's keys and over the heads */
+          }
+          lse[row] = l;
+        }
+        double total = 0.0;
+        for (int j = 0; j < nb; ++j) total += grow[j];
+        for (int j = 0; j < nb; ++j) grow[j] /= total;
+        free(x);
       }
     }
   }
