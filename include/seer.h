@@ -217,6 +217,36 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope /* host struct */, const
                            void* stream);
 
 /*
+ * Training-side forward pass (Sec. 2.3, ground truth for the self-distillation of the gate, and
+ * its efficient generation inside a flash-attention forward): dense causal attention over whole
+ * sequences that also emits the target distribution the AttnGate is trained against.
+ *
+ * For sequence i (S = seqlens ? min(seqlens[i], T) : T), query position t < S, query head hq
+ * (kv head h = hq / g):  x_s = scale * q[i,t,hq].K[i,h,s] for s = 0..t;  P_s = softmax_s(x);
+ *   out[i,t,hq] = sum_s P_s V[i,h,s];  lse[i,t,hq] = log sum_s exp(x_s);
+ *   c[hq][j]  = max of P_s over the keys s <= t of block j = [j*block_size, (j+1)*block_size)
+ *               (column-wise 1-D max pooling of the attention row);
+ *   r[h][j]   = max of c[hq][j] over the g query heads of kv head h;
+ *   gt[i,h,t,j] = r[h][j] / sum_j' r[h][j']  (sums to 1 over the blocks; 0 for blocks after t).
+ * Rows t >= S are padding: out = 0, lse = -inf, gt = 0.
+ * The block maxima are taken from the block-level row maxima of the logits that the online
+ * softmax computes anyway and are turned into probabilities once the row's lse is known.
+ * fp32 accumulation; probabilities enter the PV product rounded to bf16.
+ *
+ * q bf16 [B,T,Hq,d] contiguous; kv: contiguous addressing only (page_table must be NULL), at least
+ * T tokens per sequence; out [B,T,Hq,d] of out_dtype; lse fp32 [B,T,Hq] (may be NULL);
+ * gt fp32 [B,Hkv,T,ceil(T/block_size)].  block_size in {32, 64, 128}, d = 128, g in 1..8.
+ * Workspace: seer_attn_ground_truth_workspace_bytes.
+ */
+seer_status seer_attn_ground_truth_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int block_size,
+                                                   size_t* bytes /* host, out */);
+seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv /* host struct */,
+                                   const int32_t* seqlens /* [B] or NULL */, int B, int T, int Hq, int Hkv,
+                                   int d, int block_size, float scale, void* out, seer_dtype out_dtype,
+                                   float* lse, float* gt, void* workspace, size_t workspace_bytes,
+                                   void* stream);
+
+/*
  * Measurement aid, not part of the method: a plain streaming read of `bytes` bytes (multiple of
  * 16) from device memory `src`, no gather and no arithmetic.  Its rate is the practical HBM read
  * ceiling the decode kernels are compared with.  `sink` is 16 bytes of device memory that the
@@ -257,7 +287,9 @@ typedef enum seer_kernel_class {
   SEER_KERNEL_STREAM_READ = 4,
   SEER_KERNEL_GATE_Q = 5,
   SEER_KERNEL_KC_UPDATE = 6,
-  SEER_KERNEL_CLASSES = 7
+  SEER_KERNEL_ATTN_FWD = 7,
+  SEER_KERNEL_GT_FINALIZE = 8,
+  SEER_KERNEL_CLASSES = 9
 } seer_kernel_class;
 seer_status seer_profile_enable(int on);
 seer_status seer_profile_reset(void);

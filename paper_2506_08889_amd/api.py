@@ -21,7 +21,8 @@ KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
 KNOB_DECODE_RAGGED = 2
 KNOB_GATE_IMPL = 3
-KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read", "gate_q", "kc_update")
+KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read", "gate_q", "kc_update",
+                  "attn_fwd", "gt_finalize")
 
 
 class SeerError(RuntimeError):
@@ -85,6 +86,11 @@ def load_library():
     lib.seer_kc_update.restype = c_int
     lib.seer_kc_update.argtypes = [ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_int, c_int,
                                    c_int, c_int, c_int, c_int, c_int, c_vp, c_i64, c_i64, c_i64, c_vp]
+    lib.seer_attn_ground_truth_workspace_bytes.restype = c_int
+    lib.seer_attn_ground_truth_workspace_bytes.argtypes = [c_int] * 6 + [ctypes.POINTER(c_sz)]
+    lib.seer_attn_ground_truth.restype = c_int
+    lib.seer_attn_ground_truth.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int, c_int,
+                                           c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.seer_hbm_read_probe.restype = c_int
     lib.seer_hbm_read_probe.argtypes = [c_vp, c_sz, c_vp, c_vp]
     lib.seer_set_knob.restype = c_int
@@ -264,6 +270,53 @@ def sparse_decode_multi(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqle
                                       workspace.numel(), _stream())
     _check("seer_sparse_decode_multi", st)
     return out, lse
+
+
+def attn_ground_truth_workspace_bytes(B: int, T: int, Hq: int, Hkv: int, d: int, block_size: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check("seer_attn_ground_truth_workspace_bytes",
+           load_library().seer_attn_ground_truth_workspace_bytes(B, T, Hq, Hkv, d, block_size, ctypes.byref(n)))
+    return int(n.value)
+
+
+def attn_ground_truth(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, block_size: int, scale: float, *,
+                      seqlens: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                      lse: Optional[torch.Tensor] = None, gt: Optional[torch.Tensor] = None,
+                      out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+    """seer_attn_ground_truth.  q [B,T,Hq,d] bf16 contiguous; k/v [B,Hkv,>=T,d] bf16 views; seqlens [B]
+    int32 or None.  Returns (out [B,T,Hq,d], lse [B,T,Hq] fp32, gt [B,Hkv,T,ceil(T/block_size)] fp32)."""
+    lib = load_library()
+    _want(q, torch.bfloat16, "q")
+    if q.dim() != 4 or not q.is_contiguous():
+        raise ValueError("q must be contiguous [B,T,Hq,d]")
+    B, T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    if k.shape[0] != B or k.shape[2] < T:
+        raise ValueError("k/v must hold at least T tokens for each of the B sequences")
+    lay = _layout(k, v, None, 0)
+    if seqlens is not None:
+        _want(seqlens, torch.int32, "seqlens")
+        if not seqlens.is_contiguous() or seqlens.numel() != B:
+            raise ValueError("seqlens must be contiguous [B]")
+    nb = (T + block_size - 1) // block_size
+    if out is None:
+        out = torch.empty(B, T, Hq, d, dtype=out_dtype, device=q.device)
+    if out.dtype not in (torch.bfloat16, torch.float32) or not out.is_contiguous():
+        raise TypeError("out must be contiguous bf16 or fp32")
+    if lse is None:
+        lse = torch.empty(B, T, Hq, dtype=torch.float32, device=q.device)
+    if gt is None:
+        gt = torch.empty(B, Hkv, T, nb, dtype=torch.float32, device=q.device)
+    _want(lse, torch.float32, "lse"); _want(gt, torch.float32, "gt")
+    if not (lse.is_contiguous() and gt.is_contiguous()) or gt.shape != (B, Hkv, T, nb):
+        raise ValueError("lse and gt must be contiguous; gt [B,Hkv,T,nb]")
+    if workspace is None:
+        workspace = _workspace(attn_ground_truth_workspace_bytes(B, T, Hq, Hkv, d, block_size), q.device)
+    st = lib.seer_attn_ground_truth(_ptr(q), ctypes.byref(lay), _ptr(seqlens), B, T, Hq, Hkv, d, block_size,
+                                    ctypes.c_float(scale), _ptr(out), 0 if out.dtype == torch.bfloat16 else 1,
+                                    _ptr(lse), _ptr(gt), _ptr(workspace), workspace.numel(), _stream())
+    _check("seer_attn_ground_truth", st)
+    return out, lse, gt
 
 
 def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor, max_blocks: int,

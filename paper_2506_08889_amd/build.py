@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libseer.so")
-SOURCES = ["api.hip", "gate.hip", "decode_valu.hip", "decode_mfma.hip", "decode_merge.hip", "probe.hip", "frontend.hip"]
+SOURCES = ["api.hip", "gate.hip", "decode_valu.hip", "decode_mfma.hip", "decode_merge.hip", "probe.hip", "frontend.hip", "train_fwd.hip"]
 
 
 def hipcc() -> str:

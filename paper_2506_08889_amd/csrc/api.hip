@@ -399,6 +399,82 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope, const void* wk, const f
   return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
 }
 
+static size_t attn_gt_ws_bytes(int B, int T, int Hq, int block_size) {
+  const size_t nb = (size_t)(T + block_size - 1) / block_size, Tp = ((size_t)T + 15) / 16 * 16;
+  return align_up((size_t)B * Hq * nb * Tp * sizeof(float), 256) + align_up((size_t)B * Hq * T * sizeof(float), 256);
+}
+static bool attn_gt_sizes_ok(int B, int T, int Hq, int Hkv, seer_status* why) {
+  if (B <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) { *why = SEER_ERR_SHAPE; return false; }
+  if (B > 65535 || Hq > 65535) { *why = SEER_ERR_UNSUPPORTED; return false; }
+  return true;
+}
+
+seer_status seer_attn_ground_truth_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int block_size,
+                                                   size_t* bytes) {
+  if (!bytes) return SEER_ERR_NULL;
+  seer_status why;
+  if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
+  if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
+      (block_size != 32 && block_size != 64 && block_size != 128))
+    return SEER_ERR_UNSUPPORTED;
+  *bytes = attn_gt_ws_bytes(B, T, Hq, block_size);
+  return SEER_OK;
+}
+
+seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv, const int32_t* seqlens, int B, int T,
+                                   int Hq, int Hkv, int d, int block_size, float scale, void* out,
+                                   seer_dtype out_dtype, float* lse, float* gt, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  if (!q || !kv || !out || !gt) return SEER_ERR_NULL;
+  if (!kv->k || !kv->v) return SEER_ERR_NULL;
+  seer_status why;
+  if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
+  if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
+      (block_size != 32 && block_size != 64 && block_size != 128))
+    return SEER_ERR_UNSUPPORTED;
+  if (kv->page_table) return SEER_ERR_UNSUPPORTED;      // whole-sequence training batches are contiguous
+  if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
+  if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
+    return SEER_ERR_SHAPE;
+  if (!aligned16(kv->k) || !aligned16(kv->v) || !aligned16(q) || !aligned16(out)) return SEER_ERR_SHAPE;
+  const size_t need = attn_gt_ws_bytes(B, T, Hq, block_size);
+  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SEER_ERR_WORKSPACE;
+
+  seer::TrainFwdParams p{};
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(kv->k);
+  p.v = static_cast<const uint16_t*>(kv->v);
+  p.stride_seq = kv->stride_seq;
+  p.stride_head = kv->stride_head;
+  p.stride_token = kv->stride_token;
+  p.seqlens = seqlens;
+  p.B = B; p.T = T; p.Hq = Hq; p.Hkv = Hkv; p.g = Hq / Hkv; p.block_size = block_size;
+  p.nb = (T + block_size - 1) / block_size;
+  p.Tp = (T + 15) / 16 * 16;
+  p.scale_log2e = (float)((double)scale * 1.4426950408889634);
+  p.raw = static_cast<float*>(workspace);
+  p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                    align_up((size_t)B * Hq * p.nb * p.Tp * sizeof(float), 256));
+  p.out = out;
+  p.lse = lse;
+  p.gt = gt;
+  p.out_is_f32 = out_dtype == SEER_F32;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    Timed t(SEER_KERNEL_ATTN_FWD, s);
+    e = seer::launch_attn_fwd(p, s);
+  }
+  if (e != hipSuccess) return SEER_ERR_HIP;
+  {
+    Timed t(SEER_KERNEL_GT_FINALIZE, s);
+    e = seer::launch_gt_finalize(p, s);
+  }
+  return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
 seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return SEER_ERR_NULL;
   if (bytes < 16 || !aligned16(src) || !aligned16(sink)) return SEER_ERR_SHAPE;

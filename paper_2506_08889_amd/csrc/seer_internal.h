@@ -77,7 +77,26 @@ struct FrontKParams {
   int64_t kc_stride_batch, kc_stride_head, kc_stride_block;
 };
 
+struct TrainFwdParams {
+  const uint16_t* q;            // bf16 [B,T,Hq,128]
+  const uint16_t* k;            // contiguous KV addressing
+  const uint16_t* v;
+  int64_t stride_seq, stride_head, stride_token;
+  const int32_t* seqlens;       // [B] or nullptr
+  int32_t B, T, Hq, Hkv, g, block_size, nb;
+  int32_t Tp;                   // T rounded up to a multiple of 16: row stride of raw
+  float scale_log2e;
+  float* raw;                   // [B,Hq,nb,Tp] block maxima of the base-2 logits of every query row
+  float* lse2;                  // [B,Hq,T] base-2 log-sum-exp of every query row
+  void* out;                    // [B,T,Hq,128]
+  float* lse;                   // [B,T,Hq] or nullptr
+  float* gt;                    // [B,Hkv,T,nb]
+  int32_t out_is_f32;
+};
+
 // Launchers (each returns the hipError_t of the launch).
+hipError_t launch_attn_fwd(const TrainFwdParams& p, hipStream_t s);
+hipError_t launch_gt_finalize(const TrainFwdParams& p, hipStream_t s);
 hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s);
 hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, int cus, hipStream_t s);
 hipError_t launch_gate_score(const GateParams& p, hipStream_t s);

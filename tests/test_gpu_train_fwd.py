@@ -1,0 +1,141 @@
+"""GPU parity of the training-side forward (Sec. 2.3: causal attention + the AttnGate's ground truth)
+against the fp64 oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+D = 128
+# gt is a probability per block: fp32 logits (exact bf16 products, fp32 accumulation) and fp32
+# exp2 / log2 give ~1e-5 relative on each block probability; rows sum to 1 to fp32 rounding.
+GT_RTOL, GT_ATOL = 2e-4, 1e-7
+LSE_TOL = 1e-4
+# P enters the PV product rounded to bf16 (2^-9 relative per term, averaging down over the row)
+OUT_ATOL_F32, OUT_RTOL_ROW = 6e-3, 1e-2
+
+
+@pytest.fixture(scope="module")
+def seer():
+    import paper_2506_08889_amd as s
+    s.load_library()
+    return s
+
+
+def make(seed, B, T, Hq, Hkv, spread=1.0):
+    gen = synth.generator(DEV, seed)
+    q = synth.randn_bf16((B, T, Hq, D), DEV, gen)
+    k = synth.randn_bf16((B, Hkv, T, D), DEV, gen)
+    v = synth.randn_bf16((B, Hkv, T, D), DEV, gen)
+    if spread != 1.0:
+        q = (q.float() * spread).to(torch.bfloat16)
+    return q, k, v
+
+
+def check(seer, q, k, v, b, scale, seqlens=None, out_dtype=torch.float32):
+    out, lse, gt = seer.attn_ground_truth(q, k, v, b, scale, seqlens=seqlens, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    ro, rl, rg = oracle.attn_ground_truth(q.cpu(), k.cpu(), v.cpu(), b, scale,
+                                          seqlens=None if seqlens is None else seqlens.cpu())
+    out, lse, gt = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64), \
+        gt.cpu().numpy().astype(np.float64)
+    B, T = q.shape[0], q.shape[1]
+    S = np.full(B, T) if seqlens is None else np.minimum(seqlens.cpu().numpy(), T)
+    for i in range(B):
+        s = int(S[i])
+        # padding rows: exact zeros / -inf
+        assert (out[i, s:] == 0).all() and np.isneginf(lse[i, s:]).all() and (gt[i, :, s:] == 0).all()
+        if s == 0:
+            continue
+        np.testing.assert_allclose(lse[i, :s], rl[i, :s], rtol=0, atol=LSE_TOL)
+        np.testing.assert_allclose(gt[i, :, :s], rg[i, :, :s], rtol=GT_RTOL, atol=GT_ATOL)
+        # entries after the causal limit are exact zeros, rows sum to one
+        for t in range(0, s, max(1, s // 37)):
+            assert (gt[i, :, t, t // b + 1:] == 0).all()
+        np.testing.assert_allclose(gt[i, :, :s].sum(-1), 1.0, rtol=0, atol=2e-6)
+        err = np.abs(out[i, :s] - ro[i, :s])
+        atol = OUT_ATOL_F32 if out_dtype == torch.float32 else 1e-2
+        assert err.max() <= atol, err.max()
+        rowref = np.abs(ro[i, :s]).max(-1)
+        assert (err.max(-1) <= OUT_RTOL_ROW * np.maximum(rowref, 0.05) + 1e-6).all()
+    return out, lse, gt
+
+
+@pytest.mark.parametrize("B,T,Hq,Hkv,b", [
+    (1, 64, 1, 1, 64),          # one key tile, one block
+    (2, 200, 4, 2, 64),         # ragged tail of the last query tile and key tile
+    (1, 333, 8, 1, 32),         # g = 8, blocks of one chunk
+    (1, 517, 6, 2, 128),        # g = 3, blocks spanning two key tiles, several query tiles
+    (2, 130, 5, 5, 64),         # g = 1
+    (1, 1024, 4, 1, 64),        # 8 query tiles x 16 key tiles
+])
+def test_matches_oracle(seer, B, T, Hq, Hkv, b):
+    q, k, v = make(10 + T, B, T, Hq, Hkv)
+    check(seer, q, k, v, b, 1.0 / math.sqrt(D))
+
+
+def test_peaked_rows_and_bf16_output(seer):
+    # larger logits: rows dominated by a few keys, block maxima close to 1
+    q, k, v = make(3, 1, 400, 4, 2, spread=3.0)
+    out, lse, gt = check(seer, q, k, v, 64, 1.0 / math.sqrt(D), out_dtype=torch.bfloat16)
+    assert gt.max() > 0.5
+
+
+def test_sequence_lengths_and_padding_rows(seer):
+    q, k, v = make(4, 4, 300, 4, 2)
+    sl = torch.tensor([300, 129, 1, 0], dtype=torch.int32, device=DEV)
+    check(seer, q, k, v, 64, 0.09, seqlens=sl)
+
+
+def test_strided_kv_and_longer_cache(seer):
+    # K/V are views into a longer, interleaved cache: [B, S_alloc, Hkv, D] storage read as [B,Hkv,S,D]
+    gen = synth.generator(DEV, 5)
+    B, T, Hq, Hkv = 2, 260, 4, 2
+    q = synth.randn_bf16((B, T, Hq, D), DEV, gen)
+    kk = synth.randn_bf16((B, 320, Hkv, D), DEV, gen).permute(0, 2, 1, 3)
+    vv = synth.randn_bf16((B, 320, Hkv, D), DEV, gen).permute(0, 2, 1, 3)
+    out, lse, gt = seer.attn_ground_truth(q, kk, vv, 64, 0.09, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ro, rl, rg = oracle.attn_ground_truth(q.cpu(), kk[:, :, :T].cpu(), vv[:, :, :T].cpu(), 64, 0.09)
+    np.testing.assert_allclose(gt.cpu().numpy(), rg, rtol=GT_RTOL, atol=GT_ATOL)
+    np.testing.assert_allclose(lse.cpu().numpy(), rl, rtol=0, atol=LSE_TOL)
+    assert np.abs(out.cpu().numpy() - ro).max() <= OUT_ATOL_F32
+
+
+def test_needle_rows_put_the_mass_on_the_needle_block(seer):
+    T, b = 384, 64
+    q = torch.zeros(1, T, 2, D, dtype=torch.bfloat16, device=DEV)
+    k = torch.zeros(1, 1, T, D, dtype=torch.bfloat16, device=DEV)
+    v = synth.randn_bf16((1, 1, T, D), DEV, synth.generator(DEV, 6))
+    q[0, :, 0, 0] = 8.0
+    q[0, :, 1, 1] = 8.0
+    k[0, 0, 70, 0] = 8.0          # block 1
+    k[0, 0, 300, 1] = 8.0         # block 4
+    out, lse, gt = seer.attn_ground_truth(q, k, v, b, 0.25, out_dtype=torch.float32)
+    gt = gt.cpu().numpy()
+    # logits of the needles are 16: for t >= 300 both needle blocks carry ~all of the mass, equally
+    assert np.all(np.abs(gt[0, 0, 300:, 1] - 0.5) < 1e-3) and np.all(np.abs(gt[0, 0, 300:, 4] - 0.5) < 1e-3)
+    # 70 <= t < 300: head 0 sits on its needle (probability ~1), head 1 is still uniform (1/(t+1) per key),
+    # so the needle block gets 1 and every other visible block 1/(t+1) before normalising
+    for t in (70, 127, 128, 299):
+        nvis = t // b + 1
+        want = 1.0 / (1.0 + (nvis - 1) / (t + 1.0))
+        assert abs(gt[0, 0, t, 1] - want) < 1e-5
+    np.testing.assert_allclose(gt[0, 0, 10], [1.0, 0, 0, 0, 0, 0], atol=1e-6)
+    np.testing.assert_allclose(gt[0, 0, 69], [0.5, 0.5, 0, 0, 0, 0], atol=1e-6)
+
+
+def test_argument_errors_are_reported_before_any_launch(seer):
+    q, k, v = make(7, 1, 64, 4, 2)
+    with pytest.raises(seer.SeerError):
+        seer.attn_ground_truth(q, k, v, 48, 0.09)                   # block size not built
+    with pytest.raises(seer.SeerError):
+        seer.attn_ground_truth(q, k, v, 64, 0.09, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    with pytest.raises(seer.SeerError):
+        seer.attn_ground_truth(q[:, :, :3].contiguous(), k, v, 64, 0.09)      # 3 heads over 2 kv heads
