@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix-core peak
 
 
 def log(*a):
@@ -68,6 +69,8 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for hardware counters)")
     ap.add_argument("--dense-steps", type=int, default=5, help="timed dense flash-decode steps (0 = skip the dense baseline)")
+    ap.add_argument("--train-tokens", type=int, default=16384,
+                    help="sequence length of the training-side forward (ground-truth kernel) leg, 0 = skip")
     ap.add_argument("--also", default="c2", help="second workload reported compactly in the same line ('' = none)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -275,6 +278,42 @@ def run_workload(args, workload, seer, synth, torch, np, full):
                  "decode_tokens_per_s": B * T / (ms_mt * 1e-3)}
         del qm, out_m, lse_m, ws_m
 
+    # ---- training-side forward: causal attention + gate ground truth over one whole sequence
+    train = None
+    if full and args.train_tokens > 0 and bs % 32 == 0:
+        Tt = args.train_tokens
+        gen_t = synth.generator(dev, w.seed + 4000)
+        q_t = synth.randn_bf16((1, Tt, Hq, d), dev, gen_t)
+        k_t = synth.randn_bf16((1, Hkv, Tt, d), dev, gen_t)
+        v_t = synth.randn_bf16((1, Hkv, Tt, d), dev, gen_t)
+        nb_t = (Tt + bs - 1) // bs
+        out_t = torch.empty(1, Tt, Hq, d, dtype=torch.bfloat16, device=dev)
+        lse_t = torch.empty(1, Tt, Hq, dtype=torch.float32, device=dev)
+        gt_t = torch.empty(1, Hkv, Tt, nb_t, dtype=torch.float32, device=dev)
+        ws_t = torch.empty(seer.attn_ground_truth_workspace_bytes(1, Tt, Hq, Hkv, d, bs), dtype=torch.uint8, device=dev)
+
+        def tr(i):
+            seer.attn_ground_truth(q_t, k_t, v_t, bs, w.scale, out=out_t, lse=lse_t, gt=gt_t, workspace=ws_t)
+
+        for i in range(2):
+            tr(i)
+        seer.profile_reset()
+        seer.profile_enable(True)
+        ms_tr = timed(tr, 5)
+        seer.profile_enable(False)
+        n_f, t_f = seer.profile_read(7)
+        n_z, t_z = seer.profile_read(8)
+        seer.profile_reset()
+        flops = 4.0 * Hq * d * (Tt * (Tt + 1) / 2)          # QK^T and PV over the causal triangle
+        fwd_ms = t_f / n_f
+        tf = flops / (fwd_ms * 1e-3) / 1e12
+        train = {"workload": f"1 sequence of {Tt} tokens, {Hq} q / {Hkv} kv heads, block {bs}",
+                 "ms_per_call": ms_tr, "attn_fwd_kernel_ms": fwd_ms, "gt_finalize_kernel_ms": t_z / n_z,
+                 "causal_flops": flops,
+                 "roofline": {"bound": "mfma", "kernel": "seer_attn_fwd", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None}}
+        del q_t, k_t, v_t, out_t, lse_t, gt_t, ws_t
+
     if args.calibrate_copy_mib > 0:
         a = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         b_ = torch.empty_like(a)
@@ -327,6 +366,7 @@ def run_workload(args, workload, seer, synth, torch, np, full):
         "stream_read_GBps": stream_gbps,
         "frontend": frontend,
         "multi_token_decode": multi,
+        "training_forward": train,
         "dense": None, "speedup_vs_dense": None,
         "paper_context": "paper: up to 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware, not a target)",
     }

@@ -88,3 +88,53 @@ def test_c5_full_size_topk(bs):
 
 def test_c5_full_size_threshold_90pct():
     run_full("c5", 32, mode=seer.SELECT_THRESHOLD, keep=0.10)
+
+
+def test_training_forward_long_sequence_every_row():
+    """8192 tokens (64 query tiles x up to 128 key tiles), one group of two heads: every row of
+    out / lse / ground truth against the oracle."""
+    print("[full] training forward T=8192", flush=True)
+    gen = synth.generator(DEV, 77)
+    T, b = 8192, 64
+    q = synth.randn_bf16((1, T, 2, 128), DEV, gen)
+    k = synth.randn_bf16((1, 1, T, 128), DEV, gen)
+    v = synth.randn_bf16((1, 1, T, 128), DEV, gen)
+    out, lse, gt = seer.attn_ground_truth(q, k, v, b, 128 ** -0.5)
+    torch.cuda.synchronize()
+    ro, rl, rg = oracle.attn_ground_truth(q.cpu(), k.cpu(), v.cpu(), b, 128 ** -0.5)
+    np.testing.assert_allclose(lse.cpu().numpy(), rl, rtol=0, atol=1e-3)
+    np.testing.assert_allclose(gt.cpu().numpy(), rg, rtol=2e-4, atol=1e-7)
+    err = np.abs(out.float().cpu().numpy() - ro)
+    assert err.max() <= 1e-2 and (err.max(-1) <= 1e-2 * np.maximum(np.abs(ro).max(-1), 0.05) + 1e-6).all()
+
+
+def test_training_forward_in_the_bench_configuration_on_sampled_rows():
+    """The shape bench.py times (16384 tokens, c4's 40 / 8 heads, bf16 out): the first 512 rows against
+    the oracle run on that prefix (causality makes them independent of the rest), late rows' out / lse
+    against the decode oracle, and the properties every ground-truth row has."""
+    print("[full] training forward T=16384, 40/8 heads", flush=True)
+    w = synth.CONFIGS["c4"]
+    gen = synth.generator(DEV, w.seed + 4000)
+    T, b, Hq, Hkv = 16384, w.block_size, w.Hq, w.Hkv
+    q = synth.randn_bf16((1, T, Hq, 128), DEV, gen)
+    k = synth.randn_bf16((1, Hkv, T, 128), DEV, gen)
+    v = synth.randn_bf16((1, Hkv, T, 128), DEV, gen)
+    out, lse, gt = seer.attn_ground_truth(q, k, v, b, w.scale)
+    torch.cuda.synchronize()
+    P = 512
+    ro, rl, rg = oracle.attn_ground_truth(q[:, :P].cpu(), k[:, :, :P].cpu(), v[:, :, :P].cpu(), b, w.scale)
+    np.testing.assert_allclose(lse[:, :P].cpu().numpy(), rl, rtol=0, atol=1e-3)
+    np.testing.assert_allclose(gt[:, :, :P, :P // b].cpu().numpy(), rg, rtol=2e-4, atol=1e-7)
+    assert (gt[:, :, :P, P // b:] == 0).all()
+    assert np.abs(out[:, :P].float().cpu().numpy() - ro).max() <= 1e-2
+    kc, vc = k.cpu(), v.cpu()
+    for t in (4095, 8192, 12345, T - 1):
+        o1, l1 = oracle.sparse_decode(q[:, t].cpu().contiguous(), oracle.KVLayout(kc, vc),
+                                      torch.tensor([t + 1], dtype=torch.int32), None, None, b, w.scale)
+        np.testing.assert_allclose(lse[:, t].cpu().numpy(), l1, rtol=0, atol=1e-3)
+        assert np.abs(out[:, t].float().cpu().numpy() - o1).max() <= 1e-2
+    g = gt.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(g.sum(-1), 1.0, rtol=0, atol=5e-6)
+    rows = np.arange(T)
+    visible = (np.arange(T // b)[None, :] <= (rows // b)[:, None])
+    assert (g[0][:, ~visible] == 0).all() and (g[0][:, visible] > 0).all()
