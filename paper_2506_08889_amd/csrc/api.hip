@@ -433,6 +433,7 @@ seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv, cons
       (block_size != 32 && block_size != 64 && block_size != 128))
     return SEER_ERR_UNSUPPORTED;
   if (kv->page_table) return SEER_ERR_UNSUPPORTED;      // whole-sequence training batches are contiguous
+  if (!(scale > 0.f) || scale > 3.0e38f) return SEER_ERR_UNSUPPORTED;   // row maxima are taken before scaling
   if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
   if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
     return SEER_ERR_SHAPE;

@@ -4,8 +4,8 @@
 // probabilities once the row's log-sum-exp is known.
 //
 // Kernel 1, seer_attn_fwd_kernel: grid (query tiles of 128 rows, longest first; query head; sequence),
-// 256 threads.  A wave owns 32 query rows as two 16-row tiles and walks the keys 64 at a time (two
-// 32-key chunks).  The matrix-core formulation is the one of the decode kernel, with query rows in
+// 256 threads.  A wave owns 32 query rows as two 16-row tiles and walks the keys 64 at a time (one
+// softmax step per 64 keys, two 32-key halves for the PV product).  The matrix-core formulation is the one of the decode kernel, with query rows in
 // the place of the heads of a group (lane = 16*q + n):
 //   S^T = K Q^T   A = 16 keys x 32 features from the work-group's K tile in LDS (XOR-swizzled rows,
 //                 double-buffered: the next tile is fetched into registers during the current one
@@ -13,7 +13,9 @@
 //   softmax       lane holds 4 keys x 2 tiles of one query row; causal mask on the diagonal chunks;
 //                 the chunk maximum doubles as the block maximum (running over the chunks of a block).
 //   O^T = V^T P^T B = P^T rounded to bf16, already in operand layout; A = V^T built in registers
-//                 from coalesced row loads (8 rows x 16 bytes per lane, 16-bit interleaves).
+//                 from the work-group's V tile in LDS (8 rows x 16 bytes per lane, 16-bit interleaves).
+// K and V tiles are fetched by all 256 threads one iteration ahead, so a row crosses the memory
+// system once per work-group and its latency is covered by a whole iteration of arithmetic.
 // Kernel 2, seer_gt_finalize_kernel: per (sequence, kv head, 64 query rows): block probabilities
 // exp2(raw - lse2), maximum over the g heads, row sums, normalised rows written through an LDS
 // transpose so that both the reads (along rows) and the writes (along blocks) are coalesced.
@@ -26,8 +28,6 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
-__device__ __forceinline__ uint32_t tf_pack_lo(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }
-__device__ __forceinline__ uint32_t tf_pack_hi(uint32_t x, uint32_t y) { return (x >> 16) | (y & 0xffff0000u); }
 __device__ __forceinline__ uint32_t tf_dword(const uint4& v, int i) {
   return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
 }
@@ -46,6 +46,7 @@ constexpr int kKTile = 64;    // keys per iteration
 
 __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][kKTile * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char vbuf[2][kKTile * 256];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
@@ -87,33 +88,28 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   }
   const int ntiles = (kend + kKTile - 1) / kKTile;
 
-  // K tile staging: thread covers rows 16*u + tid/16, 16-byte chunk tid%16
+  // K / V tile staging: thread covers rows 16*u + tid/16, 16-byte chunk tid%16.  K rows are stored
+  // XOR-swizzled (operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).
   const int srow = tid >> 4, schunk = tid & 15;
-  uint4 kreg[4];
-  auto load_ktile = [&](int kt0) {
+  uint4 kreg[4], vreg[4];
+  auto load_tile = [&](int kt0) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int key = kt0 + 16 * u + srow;
       kreg[u] = make_uint4(0, 0, 0, 0);
-      if (key < p.T) kreg[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)key * st + schunk * 8);
+      vreg[u] = make_uint4(0, 0, 0, 0);
+      if (key < p.T) {
+        kreg[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)key * st + schunk * 8);
+        vreg[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)key * st + schunk * 8);
+      }
     }
   };
-  auto store_ktile = [&](int buf) {
+  auto store_tile = [&](int buf) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int row = 16 * u + srow;
       *reinterpret_cast<uint4*>(kbuf[buf] + row * 256 + ((schunk ^ (row & 15)) << 4)) = kreg[u];
-    }
-  };
-  // V rows of a 32-key chunk: load j covers key tau(q4, j) = j < 4 ? 4*q4 + j : 16 + 4*q4 + (j - 4)
-  uint4 vr[8];
-  auto load_v = [&](int key0) {
-    const uint16_t* base = vbase + n16 * 8;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int key = key0 + ((j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4));
-      vr[j] = make_uint4(0, 0, 0, 0);
-      if (key < p.T) vr[j] = *reinterpret_cast<const uint4*>(base + (int64_t)key * st);
+      *reinterpret_cast<uint4*>(vbuf[buf] + row * 256 + (schunk << 4)) = vreg[u];
     }
   };
 
@@ -125,9 +121,8 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
     for (int e = 0; e < 8; ++e) oacc[a][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   if (ntiles > 0) {
-    load_ktile(0);
-    store_ktile(0);
-    if (wave_end > 0) load_v(0);
+    load_tile(0);
+    store_tile(0);
   }
   __syncthreads();
 
@@ -136,98 +131,119 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   for (int it = 0; it < ntiles; ++it) {
     const int kt0 = it * kKTile;
     const bool more = it + 1 < ntiles;
-    if (more) load_ktile(kt0 + kKTile);
+    if (more) load_tile(kt0 + kKTile);
     const unsigned char* kt = kbuf[it & 1];
+    const unsigned char* vt = vbuf[it & 1];
 
+    if (kt0 < wave_end) {                     // wave-uniform: some row of this wave sees the tile
+      // ---- S^T = K Q^T for the four 16-key tiles; all issued before the softmax so that the
+      //      matrix core works on the later tiles while the vector units start on the first --------
+      f32x4_t sacc[2][4];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const int key0 = kt0 + 32 * c;
-      if (key0 < wave_end) {                 // wave-uniform: some row of this wave sees the chunk
-        // ---- S^T = K Q^T -----------------------------------------------------------------------
-        f32x4_t sacc[2][2];
+      for (int t = 0; t < 4; ++t) {
+        const int row = 16 * t + n16;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int kk = 0; kk < 4; ++kk) {
+          const uint4 ka = *reinterpret_cast<const uint4*>(kt + row * 256 + (((kk * 4 + q4) ^ n16) << 4));
 #pragma unroll
-          for (int t = 0; t < 2; ++t) sacc[a][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int row = 32 * c + 16 * t + n16;
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const uint4 ka = *reinterpret_cast<const uint4*>(kt + row * 256 + (((kk * 4 + q4) ^ n16) << 4));
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-              sacc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka),
-                                                                   __builtin_bit_cast(bf16x8_t, qb[a][kk]),
-                                                                   sacc[a][t], 0, 0, 0);
-          }
+          for (int a = 0; a < 2; ++a)
+            sacc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8_t, ka), __builtin_bit_cast(bf16x8_t, qb[a][kk]),
+                kk == 0 ? f32x4_t{0.f, 0.f, 0.f, 0.f} : sacc[a][t], 0, 0, 0);
         }
+      }
 
-        // ---- online softmax per query tile; lane holds keys key0 + 16t + 4*q4 + r of row qrow[a] ---
-        uint4 pb[2];
-        const int jblk = key0 / p.block_size;
-        const bool blk_start = (key0 % p.block_size) == 0;
+      // ---- online softmax over the 64 keys per query tile; lane holds keys kt0 + 16t + 4*q4 + r ------
+      uint4 pb[2][2];
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-          float x[8];
+      for (int a = 0; a < 2; ++a) {
+        // x holds the unscaled logits; scale_log2e > 0, so maxima commute with the scaling, and the
+        // scaling itself is folded into the exponent: exp2(x * s - m)
+        float x[16];
 #pragma unroll
-          for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[a][t][r] * p.scale_log2e;
-          if (key0 + 31 > wrow0 + 16 * a) {  // the diagonal passes through this chunk for some row
+          for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[a][t][r];
+        if (kt0 + 63 > wrow0 + 16 * a) {     // the diagonal passes through this tile for some row
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+          for (int t = 0; t < 4; ++t)
 #pragma unroll
-              for (int r = 0; r < 4; ++r)
-                if (key0 + 16 * t + 4 * q4 + r > qrow[a]) x[4 * t + r] = -INFINITY;
-          }
-          float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            for (int r = 0; r < 4; ++r)
+              if (kt0 + 16 * t + 4 * q4 + r > qrow[a]) x[4 * t + r] = -INFINITY;
+        }
+        // maxima of the two 32-key halves (a block may be one half), then of the tile
+        float mh[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const float* y = x + 8 * c;
+          float mx = fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7])));
           mx = fmaxf(mx, __shfl_xor(mx, 16));
           mx = fmaxf(mx, __shfl_xor(mx, 32));
-          // block maximum of the logits of this row (Sec. 2.3: the row maxima are reused)
-          bmax[a] = blk_start ? mx : fmaxf(bmax[a], mx);
-          if (q4 == 0 && qrow[a] < p.T) rawbase[(int64_t)jblk * p.Tp + qrow[a]] = bmax[a];
-
-          const float m_new = fmaxf(m_run[a], mx);
-          const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f(m_run[a] - m_ref);
-          float pr[8], psum = 0.f;
-#pragma unroll
-          for (int cc = 0; cc < 8; ++cc) {
-            pr[cc] = __builtin_amdgcn_exp2f(x[cc] - m_ref);
-            psum += pr[cc];
+          mh[c] = mx * p.scale_log2e;
+        }
+        // block maxima of the logits of this row (Sec. 2.3: the row maxima are reused)
+        if (p.block_size == 32) {
+          if (q4 == 0 && qrow[a] < p.T) {
+            const int j0 = kt0 >> 5;
+            rawbase[(int64_t)j0 * p.Tp + qrow[a]] = mh[0];
+            if (j0 + 1 < p.nb) rawbase[(int64_t)(j0 + 1) * p.Tp + qrow[a]] = mh[1];
           }
-          l_run[a] = l_run[a] * alpha + psum;
-          m_run[a] = m_new;
-          if (__ballot(alpha != 1.0f)) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) oacc[a][e] *= alpha;
-          }
-          pb[a] = make_uint4(tf_pack_bf16(pr[0], pr[1]), tf_pack_bf16(pr[2], pr[3]), tf_pack_bf16(pr[4], pr[5]),
-                             tf_pack_bf16(pr[6], pr[7]));
+        } else {
+          const float mt = fmaxf(mh[0], mh[1]);
+          bmax[a] = (kt0 % p.block_size) == 0 ? mt : fmaxf(bmax[a], mt);
+          if (q4 == 0 && qrow[a] < p.T) rawbase[(int64_t)(kt0 / p.block_size) * p.Tp + qrow[a]] = bmax[a];
         }
 
-        // ---- O^T += V^T P^T ---------------------------------------------------------------------
+        const float m_new = fmaxf(m_run[a], fmaxf(mh[0], mh[1]));
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[a] - m_ref);
+        float pr[16], psum = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < 16; ++cc) {
+          pr[cc] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[cc], p.scale_log2e, -m_ref));
+          psum += pr[cc];
+        }
+        l_run[a] = l_run[a] * alpha + psum;
+        m_run[a] = m_new;
+        if (__ballot(alpha != 1.0f)) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) oacc[a][e] *= alpha;
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          pb[a][c] = make_uint4(tf_pack_bf16(pr[8 * c + 0], pr[8 * c + 1]), tf_pack_bf16(pr[8 * c + 2], pr[8 * c + 3]),
+                                tf_pack_bf16(pr[8 * c + 4], pr[8 * c + 5]), tf_pack_bf16(pr[8 * c + 6], pr[8 * c + 7]));
+      }
+
+      // ---- O^T += V^T P^T per 32-key half: lane reads 8 keys x 16 bytes, key of slot j = tau(q4, j) =
+      //      j < 4 ? 4*q4 + j : 16 + 4*q4 + (j - 4), the order the probabilities sit in ----------------
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        uint4 vr[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int row = 32 * c + ((j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4));
+          vr[j] = *reinterpret_cast<const uint4*>(vt + row * 256 + (n16 << 4));
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           uint32_t o[4];
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
             const uint32_t x0 = tf_dword(vr[2 * jj], e >> 1), x1 = tf_dword(vr[2 * jj + 1], e >> 1);
-            o[jj] = (e & 1) ? tf_pack_hi(x0, x1) : tf_pack_lo(x0, x1);
+            o[jj] = __builtin_amdgcn_perm(x1, x0, (e & 1) ? 0x07060302u : 0x05040100u);
           }
           const uint4 va = make_uint4(o[0], o[1], o[2], o[3]);
 #pragma unroll
           for (int a = 0; a < 2; ++a)
             oacc[a][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va),
-                                                                 __builtin_bit_cast(bf16x8_t, pb[a]), oacc[a][e],
+                                                                 __builtin_bit_cast(bf16x8_t, pb[a][c]), oacc[a][e],
                                                                  0, 0, 0);
         }
-        if (key0 + 32 < wave_end) load_v(key0 + 32);
       }
     }
 
-    if (more) store_ktile((it + 1) & 1);
+    if (more) store_tile((it + 1) & 1);
     __syncthreads();
   }
 
