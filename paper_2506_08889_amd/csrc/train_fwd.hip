@@ -21,6 +21,8 @@
 // transpose so that both the reads (along rows) and the writes (along blocks) are coalesced.
 #include "seer_internal.h"
 
+#include <type_traits>
+
 namespace seer {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -44,6 +46,8 @@ constexpr int kKTile = 64;    // keys per iteration
 
 }  // namespace
 
+// ROWS128: stride_token == 128 elements (rows back to back), so row offsets are immediates.
+template <bool ROWS128>
 __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][kKTile * 256];
   __shared__ __attribute__((aligned(16))) unsigned char vbuf[2][kKTile * 256];
@@ -77,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 
   const uint16_t* kbase = p.k + (int64_t)i * p.stride_seq + (int64_t)hk * p.stride_head;
   const uint16_t* vbase = p.v + (int64_t)i * p.stride_seq + (int64_t)hk * p.stride_head;
-  const int64_t st = p.stride_token;
+  const int64_t st = ROWS128 ? (int64_t)kHeadDim : p.stride_token;
   int kend = r0 + kQTile;                    // keys [0, kend) matter to this work-group
   kend = kend < S ? kend : S;
   int wave_end = wrow0 + 32;                 // keys [0, wave_end) matter to this wave
@@ -92,15 +96,26 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   // XOR-swizzled (operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).
   const int srow = tid >> 4, schunk = tid & 15;
   uint4 kreg[4], vreg[4];
+  const uint16_t* kptr = kbase + (int64_t)srow * st + schunk * 8;      // this thread's row of the tile at key 0
+  const uint16_t* vptr = vbase + (int64_t)srow * st + schunk * 8;
   auto load_tile = [&](int kt0) {
+    const uint16_t* kp = kptr + (int64_t)kt0 * st;
+    const uint16_t* vp = vptr + (int64_t)kt0 * st;
+    if (kt0 + kKTile <= p.T) {               // work-group-uniform: every row of the tile exists
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int key = kt0 + 16 * u + srow;
-      kreg[u] = make_uint4(0, 0, 0, 0);
-      vreg[u] = make_uint4(0, 0, 0, 0);
-      if (key < p.T) {
-        kreg[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)key * st + schunk * 8);
-        vreg[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)key * st + schunk * 8);
+      for (int u = 0; u < 4; ++u) {
+        kreg[u] = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
+        vreg[u] = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        kreg[u] = make_uint4(0, 0, 0, 0);
+        vreg[u] = make_uint4(0, 0, 0, 0);
+        if (kt0 + 16 * u + srow < p.T) {
+          kreg[u] = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
+          vreg[u] = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
+        }
       }
     }
   };
@@ -128,14 +143,10 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 
   float* rawbase = p.raw + ((int64_t)i * p.Hq + h) * p.nb * (int64_t)p.Tp;
 
-  for (int it = 0; it < ntiles; ++it) {
-    const int kt0 = it * kKTile;
-    const bool more = it + 1 < ntiles;
-    if (more) load_tile(kt0 + kKTile);
-    const unsigned char* kt = kbuf[it & 1];
-    const unsigned char* vt = vbuf[it & 1];
-
-    if (kt0 < wave_end) {                     // wave-uniform: some row of this wave sees the tile
+  // One 64-key tile for this wave.  MASKED: the tile may hold keys beyond some row of the wave (only
+  // the last tile or two of a wave's range); interior tiles carry no masking code at all.
+  auto tile_body = [&](auto masked_tag, const int kt0, const unsigned char* kt, const unsigned char* vt) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
       // ---- S^T = K Q^T for the four 16-key tiles; all issued before the softmax so that the
       //      matrix core works on the later tiles while the vector units start on the first --------
       f32x4_t sacc[2][4];
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
         for (int t = 0; t < 4; ++t)
 #pragma unroll
           for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[a][t][r];
-        if (kt0 + 63 > wrow0 + 16 * a) {     // the diagonal passes through this tile for some row
+        if (MASKED && kt0 + 63 > wrow0 + 16 * a) {     // the diagonal passes through this tile for some row
 #pragma unroll
           for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -241,6 +252,18 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
                                                                  0, 0, 0);
         }
       }
+  };
+
+  for (int it = 0; it < ntiles; ++it) {
+    const int kt0 = it * kKTile;
+    const bool more = it + 1 < ntiles;
+    if (more) load_tile(kt0 + kKTile);
+    const unsigned char* kt = kbuf[it & 1];
+    const unsigned char* vt = vbuf[it & 1];
+
+    if (kt0 < wave_end) {                     // wave-uniform: some row of this wave sees the tile
+      if (kt0 + 63 > wrow0) tile_body(std::true_type{}, kt0, kt, vt);
+      else tile_body(std::false_type{}, kt0, kt, vt);
     }
 
     if (more) store_tile((it + 1) & 1);
@@ -349,7 +372,10 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
 
 hipError_t launch_attn_fwd(const TrainFwdParams& p, hipStream_t s) {
   const dim3 grid((p.T + kQTile - 1) / kQTile, p.Hq, p.B);
-  hipLaunchKernelGGL(seer_attn_fwd_kernel, grid, dim3(256), 0, s, p);
+  if (p.stride_token == kHeadDim)
+    hipLaunchKernelGGL(seer_attn_fwd_kernel<true>, grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL(seer_attn_fwd_kernel<false>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
