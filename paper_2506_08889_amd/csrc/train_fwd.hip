@@ -14,8 +14,9 @@
 //                 the chunk maximum doubles as the block maximum (running over the chunks of a block).
 //   O^T = V^T P^T B = P^T rounded to bf16, already in operand layout; A = V^T built in registers
 //                 from the work-group's V tile in LDS (8 rows x 16 bytes per lane, 16-bit interleaves).
-// K and V tiles are fetched by all 256 threads one iteration ahead, so a row crosses the memory
-// system once per work-group and its latency is covered by a whole iteration of arithmetic.
+// K and V tiles are fetched by all 256 threads one iteration ahead, directly into the other LDS stage,
+// so a row crosses the memory system once per work-group and its latency is covered by a whole
+// iteration of arithmetic.
 // Kernel 2, seer_gt_finalize_kernel: per (sequence, kv head, 64 query rows): block probabilities
 // exp2(raw - lse2), maximum over the g heads, row sums, normalised rows written through an LDS
 // transpose so that both the reads (along rows) and the writes (along blocks) are coalesced.
@@ -41,6 +42,8 @@ __device__ __forceinline__ uint32_t tf_pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
+#define SEER_LDS_PTR(ptr) ((__attribute__((address_space(3))) void*)(ptr))
+
 constexpr int kQTile = 128;   // query rows per work-group
 constexpr int kKTile = 64;    // keys per iteration
 
@@ -49,8 +52,12 @@ constexpr int kKTile = 64;    // keys per iteration
 // ROWS128: stride_token == 128 elements (rows back to back), so row offsets are immediates.
 template <bool ROWS128>
 __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p) {
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][kKTile * 256];
-  __shared__ __attribute__((aligned(16))) unsigned char vbuf[2][kKTile * 256];
+  // Two stages of the K and V tiles, as four separate arrays: the compiler then knows that the
+  // asynchronous fills of one stage cannot touch the stage being read.
+  __shared__ __attribute__((aligned(16))) unsigned char kbuf_a[kKTile * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char kbuf_b[kKTile * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char vbuf_a[kKTile * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char vbuf_b[kKTile * 256];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
@@ -92,39 +99,40 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   }
   const int ntiles = (kend + kKTile - 1) / kKTile;
 
-  // K / V tile staging: thread covers rows 16*u + tid/16, 16-byte chunk tid%16.  K rows are stored
-  // XOR-swizzled (operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).
+  // K / V tile staging.  Thread (srow = tid/16, schunk = tid%16) owns the 16-byte slot `schunk` of rows
+  // 16*u + srow of a tile.  K rows are kept XOR-swizzled (slot s of row r holds chunk s ^ (r & 15):
+  // operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).  Whole tiles are
+  // fetched straight into LDS (global_load_lds: a wave fills 1 KiB = its 4 rows, lane l at +16*l, so
+  // the swizzle is applied to the global address); no staging registers, no LDS store instructions.
+  // The last tile of a sequence whose length is not a multiple of 64 goes through registers with its
+  // missing rows zeroed.
   const int srow = tid >> 4, schunk = tid & 15;
-  uint4 kreg[4], vreg[4];
-  const uint16_t* kptr = kbase + (int64_t)srow * st + schunk * 8;      // this thread's row of the tile at key 0
+  const int wave_rows = __builtin_amdgcn_readfirstlane(wave) * 4;
+  const uint16_t* kptr = kbase + (int64_t)srow * st + ((schunk ^ (srow & 15)) * 8);
   const uint16_t* vptr = vbase + (int64_t)srow * st + schunk * 8;
-  auto load_tile = [&](int kt0) {
+  auto fetch_tile = [&](int kt0, unsigned char* kdst, unsigned char* vdst) {
     const uint16_t* kp = kptr + (int64_t)kt0 * st;
     const uint16_t* vp = vptr + (int64_t)kt0 * st;
     if (kt0 + kKTile <= p.T) {               // work-group-uniform: every row of the tile exists
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        kreg[u] = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
-        vreg[u] = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
+        __builtin_amdgcn_global_load_lds(kp + (int64_t)(16 * u) * st, SEER_LDS_PTR(kdst + (16 * u + wave_rows) * 256),
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vp + (int64_t)(16 * u) * st, SEER_LDS_PTR(vdst + (16 * u + wave_rows) * 256),
+                                         16, 0, 0);
       }
     } else {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        kreg[u] = make_uint4(0, 0, 0, 0);
-        vreg[u] = make_uint4(0, 0, 0, 0);
+        uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
         if (kt0 + 16 * u + srow < p.T) {
-          kreg[u] = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
-          vreg[u] = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
+          kr = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
+          vr = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
         }
+        const int row = 16 * u + srow;
+        *reinterpret_cast<uint4*>(kdst + row * 256 + (schunk << 4)) = kr;     // kr already is the swizzled chunk
+        *reinterpret_cast<uint4*>(vdst + row * 256 + (schunk << 4)) = vr;
       }
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = 16 * u + srow;
-      *reinterpret_cast<uint4*>(kbuf[buf] + row * 256 + ((schunk ^ (row & 15)) << 4)) = kreg[u];
-      *reinterpret_cast<uint4*>(vbuf[buf] + row * 256 + (schunk << 4)) = vreg[u];
     }
   };
 
@@ -135,10 +143,8 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 #pragma unroll
     for (int e = 0; e < 8; ++e) oacc[a][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  if (ntiles > 0) {
-    load_tile(0);
-    store_tile(0);
-  }
+  if (ntiles > 0) fetch_tile(0, kbuf_a, vbuf_a);
+  __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): the fills have landed
   __syncthreads();
 
   float* rawbase = p.raw + ((int64_t)i * p.Hq + h) * p.nb * (int64_t)p.Tp;
@@ -254,20 +260,21 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
       }
   };
 
-  for (int it = 0; it < ntiles; ++it) {
+  // One iteration: start the fill of the other stage, work on this one, wait for the fill, barrier.
+  auto iteration = [&](const int it, const unsigned char* kt, const unsigned char* vt, unsigned char* knext,
+                       unsigned char* vnext) {
     const int kt0 = it * kKTile;
-    const bool more = it + 1 < ntiles;
-    if (more) load_tile(kt0 + kKTile);
-    const unsigned char* kt = kbuf[it & 1];
-    const unsigned char* vt = vbuf[it & 1];
-
+    if (it + 1 < ntiles) fetch_tile(kt0 + kKTile, knext, vnext);
     if (kt0 < wave_end) {                     // wave-uniform: some row of this wave sees the tile
       if (kt0 + 63 > wrow0) tile_body(std::true_type{}, kt0, kt, vt);
       else tile_body(std::false_type{}, kt0, kt, vt);
     }
-
-    if (more) store_tile((it + 1) & 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     __syncthreads();
+  };
+  for (int it = 0; it < ntiles; it += 2) {
+    iteration(it, kbuf_a, vbuf_a, kbuf_b, vbuf_b);
+    if (it + 1 < ntiles) iteration(it + 1, kbuf_b, vbuf_b, kbuf_a, vbuf_a);
   }
 
   // ---- results: lane (n16, q4) holds O[row n16 of tile a][32*q4 + 8*r + e] in oacc[a][e][r] ---------
