@@ -75,7 +75,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus must be 1. "
-                 "The path shards over (batch, kv-head) groups without communication; see DESIGN.md.")
+                 "The path shards over (batch, kv-head) groups without any communication.")
 
     import numpy as np
     import torch

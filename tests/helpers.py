@@ -10,7 +10,7 @@ from oracle import KVLayout
 
 # Tolerances.  Contract (benchmark definition): |out - ref| <= 1e-2 elementwise and
 # max|out - ref| <= 1e-2 * max|ref| per row for bf16-in / fp32-accumulate outputs, lse within
-# 1e-3.  The fp32-output runs are held to a much tighter bar (derived in the design doc): inputs are
+# 1e-3.  The fp32-output runs are held to a much tighter bar, derived from the arithmetic: inputs are
 # exact bf16, logits and outputs accumulate in fp32, and the MFMA kernel feeds the probabilities
 # to the PV product as hi + lo bf16 pairs (2^-17 relative), so 2e-4 absolute / 4e-4 row-relative
 # holds with margin and catches a dropped block or token that the 1e-2 contract would let through.
