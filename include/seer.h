@@ -96,6 +96,15 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
                                         size_t* bytes /* host, out */);
 
 /*
+ * How the decode calls will cut the block lists for these sizes under the current knobs (host call,
+ * no device work): num_splits slices of blocks_per_split list entries each, the partition along
+ * num_split of Sec. 3.3.  num_splits * blocks_per_split >= max_blocks; num_splits == 1 means no
+ * merge kernel is launched.
+ */
+seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, int* num_splits /* host, out */,
+                             int* blocks_per_split /* host, out */);
+
+/*
  * AttnGate block selection (Eq. 1c; Sec. 3.1; Sec. 3.2).
  *
  * For every (sequence i, kv head h), with S = seqlens[i], nfull = S / block_size full blocks,

@@ -66,6 +66,8 @@ def load_library():
     lib.seer_gate_workspace_bytes.argtypes = [c_int, c_int, c_int, ctypes.POINTER(c_sz)]
     lib.seer_decode_workspace_bytes.restype = c_int
     lib.seer_decode_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, ctypes.POINTER(c_sz)]
+    lib.seer_decode_plan.restype = c_int
+    lib.seer_decode_plan.argtypes = [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_int)]
     lib.seer_gate_select.restype = c_int
     lib.seer_gate_select.argtypes = [c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_int, c_int, c_int, c_int,
                                      c_int, c_int, ctypes.c_int32, c_vp, ctypes.c_double, c_vp, c_vp,
@@ -141,6 +143,14 @@ def decode_workspace_bytes(B: int, Hq: int, Hkv: int, d: int, max_blocks: int) -
     _check("seer_decode_workspace_bytes",
            load_library().seer_decode_workspace_bytes(B, Hq, Hkv, d, max_blocks, ctypes.byref(n)))
     return int(n.value)
+
+
+def decode_plan(B: int, Hkv: int, max_blocks: int, block_size: int):
+    """seer_decode_plan: (num_splits, blocks_per_split) the decode calls will use for these sizes."""
+    ns, per = ctypes.c_int(0), ctypes.c_int(0)
+    _check("seer_decode_plan",
+           load_library().seer_decode_plan(B, Hkv, max_blocks, block_size, ctypes.byref(ns), ctypes.byref(per)))
+    return int(ns.value), int(per.value)
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor:

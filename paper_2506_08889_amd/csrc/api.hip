@@ -227,6 +227,15 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
   return SEER_OK;
 }
 
+seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, int* num_splits,
+                             int* blocks_per_split) {
+  if (!num_splits || !blocks_per_split) return SEER_ERR_NULL;
+  if (B <= 0 || Hkv <= 0 || max_blocks <= 0) return SEER_ERR_SHAPE;
+  if (!block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  plan_splits(B, Hkv, max_blocks, block_size, num_splits, blocks_per_split);
+  return SEER_OK;
+}
+
 seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t kc_stride_batch,
                              int64_t kc_stride_head, int64_t kc_stride_block, const int32_t* seqlens,
                              int B, int Hkv, int Dg, int nb_max, int block_size, seer_select_mode mode,

@@ -123,3 +123,73 @@ def test_knobs_roundtrip():
         seer.set_knob(0, 9)
     with pytest.raises(seer.SeerError):
         seer.set_knob(42, 1)
+
+
+def test_split_plan_properties_on_the_host():
+    """The planner is host logic: whatever the sizes and knobs, the slices cover the list capacity,
+    a slice holds at least 4 entries (or the whole list), there are at most 256 slices, and the plan
+    never needs more workspace than the size query hands out."""
+    import itertools
+    for knob in (0, 1, 2, 3):
+        seer.set_knob(knob, 0)
+    try:
+        for ragged, forced in itertools.product((0, 1), (0, 1, 3, 64, 1000)):
+            seer.set_knob(2, ragged)
+            seer.set_knob(1, forced)
+            for B, Hkv, nb, bs in itertools.product((1, 4, 16, 32, 64, 300), (1, 2, 8), (1, 3, 13, 64, 205, 2048, 5000),
+                                                    (16, 64, 128)):
+                ns, per = seer.decode_plan(B, Hkv, nb, bs)
+                assert 1 <= ns <= 256 and per >= 1
+                assert ns * per >= nb and (ns - 1) * per < nb          # covers the list, no empty last slice
+                assert per >= min(4, nb) or ns == 1
+                if forced and not ragged:
+                    assert ns <= forced
+        seer.set_knob(1, 0)
+        seer.set_knob(2, 0)
+        # equal-length lists: no cut when there are at least as many groups as compute units, and short
+        # lists stay whole when cutting saves less than a merge launch
+        assert seer.decode_plan(64, 8, 205, 64) == (1, 205)
+        assert seer.decode_plan(32, 8, 51, 64)[0] == 1
+        assert seer.decode_plan(16, 8, 13, 64)[0] == 1
+        assert seer.decode_plan(16, 8, 64, 64)[0] == 2
+        assert seer.decode_plan(1, 8, 256, 64)[0] == 32
+    finally:
+        for knob in (0, 1, 2, 3):
+            seer.set_knob(knob, 0)
+    with pytest.raises(seer.SeerError):
+        seer.decode_plan(0, 8, 16, 64)
+    with pytest.raises(seer.SeerError):
+        seer.decode_plan(1, 8, 16, 48)
+
+
+def test_training_forward_argument_errors_on_the_host():
+    lib = seer.load_library()
+    n = seer.attn_ground_truth_workspace_bytes(1, 1000, 8, 2, 128, 64)
+    assert n >= 8 * 16 * 1008 * 4 + 8 * 1000 * 4 and n % 256 == 0
+    for bad in ((0, 64, 8, 2, 128, 64), (1, 0, 8, 2, 128, 64), (1, 64, 7, 2, 128, 64)):
+        with pytest.raises(seer.SeerError) as e:
+            seer.attn_ground_truth_workspace_bytes(*bad)
+        assert e.value.status == -2
+    for bad in ((1, 64, 8, 2, 64, 64), (1, 64, 8, 2, 128, 16), (1, 64, 18, 2, 128, 64)):
+        with pytest.raises(seer.SeerError) as e:
+            seer.attn_ground_truth_workspace_bytes(*bad)
+        assert e.value.status == -3
+    import ctypes
+    from paper_2506_08889_amd.api import _KVLayout
+    P = ctypes.c_void_p(4096)
+    lay = _KVLayout()
+    lay.k, lay.v = 4096, 8192
+    lay.stride_seq, lay.stride_head, lay.stride_token = 2 * 64 * 128, 64 * 128, 128
+
+    def call(q=P, B=1, T=64, Hq=8, Hkv=2, d=128, bs=64, scale=0.1, out=P, gt=P, ws=P, wsb=1 << 30, layout=lay):
+        return lib.seer_attn_ground_truth(q, ctypes.byref(layout), None, B, T, Hq, Hkv, d, bs, ctypes.c_float(scale),
+                                          out, 0, None, gt, ws, wsb, None)
+    assert call(q=None) == -1 and call(gt=None) == -1
+    assert call(T=0) == -2 and call(Hq=7) == -2
+    assert call(bs=48) == -3 and call(scale=0.0) == -3 and call(scale=-1.0) == -3
+    assert call(ws=None) == -4 and call(wsb=1024) == -4
+    paged = _KVLayout()
+    paged.k, paged.v = 4096, 8192
+    paged.stride_seq, paged.stride_head, paged.stride_token = 2 * 64 * 128, 64 * 128, 128
+    paged.page_table, paged.max_pages, paged.page_size = 4096, 1, 64
+    assert call(layout=paged) == -3
