@@ -338,17 +338,35 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
   for (int hh = 0; hh < kMaxGroup; ++hh)
     l2[hh] = (hh < g && real) ? p.lse2[((int64_t)i * p.Hq + hk * g + hh) * p.T + t] : 0.f;
   const float* raw0 = p.raw + ((int64_t)i * p.Hq + (int64_t)hk * g) * p.nb * (int64_t)p.Tp;
-  auto block_prob = [&](int j) -> float {   // max over the heads of the block's largest probability
-    float r = 0.f;
-    for (int hh = 0; hh < g; ++hh) {
-      const float x = raw0[((int64_t)hh * p.nb + j) * p.Tp + t];
-      r = fmaxf(r, exp2f(x - l2[hh]));
+  // N blocks at once for this row: every load is issued (index clamped) before the first exponential,
+  // so a thread keeps N * g reads in flight; blocks the row cannot see give 0.
+  auto block_probs = [&](auto n_tag, const int (&js)[decltype(n_tag)::value], float (&out)[decltype(n_tag)::value]) {
+    constexpr int N = decltype(n_tag)::value;
+    float x[N][kMaxGroup];
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      const int j = js[u] < nvis ? js[u] : 0;
+#pragma unroll
+      for (int hh = 0; hh < kMaxGroup; ++hh)
+        x[u][hh] = (hh < g && real) ? raw0[((int64_t)hh * p.nb + j) * p.Tp + t] : -INFINITY;
     }
-    return r;
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+      float r = 0.f;
+#pragma unroll
+      for (int hh = 0; hh < kMaxGroup; ++hh)
+        if (hh < g) r = fmaxf(r, exp2f(x[u][hh] - l2[hh]));
+      out[u] = js[u] < nvis ? r : 0.f;
+    }
   };
 
   float sum = 0.f;
-  for (int j = part; j < nvis; j += 4) sum += block_prob(j);
+  for (int j = part; j < nvis_tile; j += 16) {      // blocks j, j+4, j+8, j+12 (the four parts interleave)
+    const int js[4] = {j, j + 4, j + 8, j + 12};
+    float v[4];
+    block_probs(std::integral_constant<int, 4>{}, js, v);
+    sum += (v[0] + v[1]) + (v[2] + v[3]);
+  }
   part_sum[part][tq] = sum;
   __syncthreads();
   const float total = part_sum[0][tq] + part_sum[1][tq] + part_sum[2][tq] + part_sum[3][tq];
@@ -358,9 +376,15 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
   for (int j0 = 0; j0 < p.nb; j0 += 64) {
     if (j0 < nvis_tile) {
       // rows of the tile in parallel, 16 blocks per thread; then transposed out
-      for (int u = 0; u < 16; ++u) {
-        const int jj = part * 16 + u, j = j0 + jj;
-        tile[tq][jj] = (j < nvis) ? block_prob(j) * inv : 0.f;
+#pragma unroll
+      for (int u0 = 0; u0 < 16; u0 += 8) {
+        int js[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) js[u] = j0 + part * 16 + u0 + u;
+        float v[8];
+        block_probs(std::integral_constant<int, 8>{}, js, v);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) tile[tq][part * 16 + u0 + u] = v[u] * inv;
       }
       __syncthreads();
       for (int u = 0; u < 16; ++u) {
