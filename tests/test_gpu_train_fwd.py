@@ -68,6 +68,8 @@ def check(seer, q, k, v, b, scale, seqlens=None, out_dtype=torch.float32):
 
 
 @pytest.mark.parametrize("B,T,Hq,Hkv,b", [
+    (1, 1, 2, 1, 32),           # a single token
+    (3, 65, 2, 2, 128),         # one token past a tile, block larger than the sequence
     (1, 64, 1, 1, 64),          # one key tile, one block
     (2, 200, 4, 2, 64),         # ragged tail of the last query tile and key tile
     (1, 333, 8, 1, 32),         # g = 8, blocks of one chunk
