@@ -141,3 +141,34 @@ def test_argument_errors_are_reported_before_any_launch(seer):
         seer.attn_ground_truth(q, k, v, 64, 0.09, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
     with pytest.raises(seer.SeerError):
         seer.attn_ground_truth(q[:, :, :3].contiguous(), k, v, 64, 0.09)      # 3 heads over 2 kv heads
+
+
+def test_randomised_shapes_lengths_and_layouts(seer):
+    """24 random configurations: sequence counts, lengths around tile and block edges, group sizes,
+    block sizes, per-sequence lengths (including empty), logit spreads and a strided K/V view."""
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        B = int(rng.integers(1, 4))
+        T = int(rng.choice([1, 31, 33, 63, 64, 65, 127, 128, 129, 191, 257, 300, 449]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        g = int(rng.choice([1, 2, 4, 5, 8]))
+        b = int(rng.choice([32, 64, 128]))
+        spread = float(rng.choice([0.5, 1.0, 2.0]))
+        strided = bool(rng.integers(0, 2))
+        seed = 500 + case
+        print(f"[random] case {case}: B={B} T={T} Hkv={Hkv} g={g} b={b} spread={spread} strided={strided}", flush=True)
+        gen = synth.generator(DEV, seed)
+        q = (synth.randn_bf16((B, T, Hkv * g, D), DEV, gen).float() * spread).to(torch.bfloat16)
+        if strided:
+            k = synth.randn_bf16((B, T + 7, Hkv, D), DEV, gen).permute(0, 2, 1, 3)[:, :, :T]
+            v = synth.randn_bf16((B, T + 7, Hkv, D), DEV, gen).permute(0, 2, 1, 3)[:, :, :T]
+        else:
+            k = synth.randn_bf16((B, Hkv, T, D), DEV, gen)
+            v = synth.randn_bf16((B, Hkv, T, D), DEV, gen)
+        sl = None
+        if rng.integers(0, 2):
+            sl = torch.tensor(rng.integers(0, T + 1, size=B), dtype=torch.int32, device=DEV)
+        out_dtype = torch.float32 if rng.integers(0, 2) else torch.bfloat16
+        if spread > 1.0 and out_dtype == torch.bfloat16:
+            out_dtype = torch.float32          # the 1e-2 bf16 bar is stated for unit-variance logits
+        check(seer, q, k, v, b, 1.0 / math.sqrt(D), seqlens=sl, out_dtype=out_dtype)
