@@ -5,6 +5,8 @@
  *
  * Workload: batch 2, 8 query / 2 kv heads, head dim 128, block 64, sequence lengths 1000 and 333
  * (both end in a partial block), token budget 512; inputs from a fixed linear congruential generator.
+ * Then the training-side forward on the first 200 tokens of the same tensors (queries drawn afresh),
+ * second sequence cut to 77 tokens.
  */
 #include <hip/hip_runtime_api.h>
 #include <math.h>
@@ -25,6 +27,8 @@ int oracle_gate_select(const uint16_t*, const uint16_t*, int64_t, int64_t, int64
                        int, int, int32_t, const int32_t*, double, int32_t*, int32_t*, int, double*);
 int oracle_sparse_decode(const uint16_t*, const oracle_kv_t*, const int32_t*, const int32_t*, const int32_t*, int, int,
                          int, int, int, int, float, double*, double*, const uint8_t*);
+int oracle_attn_ground_truth(const uint16_t*, const oracle_kv_t*, const int32_t*, int, int, int, int, int, int, float,
+                             double*, double*, double*);
 
 #define CHECK_HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "HIP error %d at %s:%d\n", (int)e_, __FILE__, __LINE__); return 2; } } while (0)
 #define CHECK_SEER(x) do { seer_status s_ = (x); if (s_ != SEER_OK) { fprintf(stderr, "%s -> %s\n", #x, seer_status_string(s_)); return 3; } } while (0)
@@ -95,6 +99,42 @@ int main(void) {
          cnt[0], cnt[Hkv], max_err, max_lse);
   (void)from_bf16;
   if (!(max_err <= 2e-4) || !(max_lse <= 1e-4)) { fprintf(stderr, "outside tolerance\n"); return 6; }
+
+  /* ---- training-side forward: causal attention + ground truth over T tokens of the same K/V ---- */
+  {
+    enum { T = 200, NBT = (T + BS - 1) / BS };
+    const int32_t tlens[B] = {T, 77};
+    const size_t ntq = (size_t)B * T * Hq * D, ngt = (size_t)B * Hkv * T * NBT;
+    uint16_t* tq = malloc(ntq * 2);
+    fill(tq, ntq, 1.f);
+    double *r_out = malloc(ntq * sizeof(double)), *r_lse = malloc((size_t)B * T * Hq * sizeof(double)),
+           *r_gt = malloc(ngt * sizeof(double));
+    if (oracle_attn_ground_truth(tq, &okv, tlens, B, T, Hq, Hkv, D, BS, scale, r_out, r_lse, r_gt)) return 4;
+    void *dtq, *dtl, *dto, *dtlse, *dgt, *ws_t;
+    size_t wst = 0;
+    CHECK_SEER(seer_attn_ground_truth_workspace_bytes(B, T, Hq, Hkv, D, BS, &wst));
+    CHECK_HIP(hipMalloc(&dtq, ntq * 2)); CHECK_HIP(hipMalloc(&dtl, sizeof tlens)); CHECK_HIP(hipMalloc(&dto, ntq * 4));
+    CHECK_HIP(hipMalloc(&dtlse, (size_t)B * T * Hq * 4)); CHECK_HIP(hipMalloc(&dgt, ngt * 4)); CHECK_HIP(hipMalloc(&ws_t, wst));
+    CHECK_HIP(hipMemcpy(dtq, tq, ntq * 2, hipMemcpyHostToDevice)); CHECK_HIP(hipMemcpy(dtl, tlens, sizeof tlens, hipMemcpyHostToDevice));
+    CHECK_SEER(seer_attn_ground_truth(dtq, &kv, dtl, B, T, Hq, Hkv, D, BS, scale, dto, SEER_F32, dtlse, dgt, ws_t, wst, stream));
+    CHECK_HIP(hipStreamSynchronize(stream));
+    float *t_out = malloc(ntq * 4), *t_lse = malloc((size_t)B * T * Hq * 4), *t_gt = malloc(ngt * 4);
+    CHECK_HIP(hipMemcpy(t_out, dto, ntq * 4, hipMemcpyDeviceToHost)); CHECK_HIP(hipMemcpy(t_lse, dtlse, (size_t)B * T * Hq * 4, hipMemcpyDeviceToHost));
+    CHECK_HIP(hipMemcpy(t_gt, dgt, ngt * 4, hipMemcpyDeviceToHost));
+    double e_out = 0.0, e_lse = 0.0, e_gt = 0.0;
+    for (size_t i = 0; i < ntq; ++i) { double e = fabs((double)t_out[i] - r_out[i]); if (e > e_out) e_out = e; }
+    for (size_t i = 0; i < (size_t)B * T * Hq; ++i) {
+      if (isinf(r_lse[i])) { if (!(isinf(t_lse[i]) && t_lse[i] < 0)) return 8; continue; }
+      double e = fabs((double)t_lse[i] - r_lse[i]); if (e > e_lse) e_lse = e;
+    }
+    for (size_t i = 0; i < ngt; ++i) {
+      double e = fabs((double)t_gt[i] - r_gt[i]) / (fabs(r_gt[i]) + 1e-3);
+      if (e > e_gt) e_gt = e;
+    }
+    printf("c_abi_check: training forward max |out - oracle| = %.3e, |lse| = %.3e, ground truth rel = %.3e\n", e_out, e_lse, e_gt);
+    if (!(e_out <= 6e-3) || !(e_lse <= 1e-4) || !(e_gt <= 2e-4)) { fprintf(stderr, "training forward outside tolerance\n"); return 8; }
+    if (seer_attn_ground_truth(dtq, &kv, dtl, B, T, Hq, Hkv, D, 48, scale, dto, SEER_F32, dtlse, dgt, ws_t, wst, stream) != SEER_ERR_UNSUPPORTED) return 7;
+  }
 
   /* error paths need no device work */
   if (seer_sparse_decode(NULL, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, stream) != SEER_ERR_NULL) return 7;
