@@ -28,7 +28,7 @@
  *     is launched.  Data-dependent conditions on the device are defined behaviour, not
  *     errors (see each call).
  *   - Supported sizes: head dim d = 128, gate dim Dg = 128, block_size in {16, 32, 64, 128}
- *     (64 and 128 are the tuned ones; 16 runs on the vector-ALU kernel), group size Hq/Hkv
+ *     (64 and 128 are the tuned ones), group size Hq/Hkv
  *     in 1..8, at most 65535 sequences and kv heads.
  */
 #ifndef SEER_H
@@ -171,7 +171,7 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv /* host s
  * selections of several queries is left to the caller).  Query t alone equals seer_sparse_decode on a
  * sequence of length seqlens[i]-q_len+1+t.
  * q bf16 [B,q_len,Hq,d]; out [B,q_len,Hq,d]; lse fp32 [B,q_len,Hq].  q_len * (Hq/Hkv) <= 16 and
- * block_size a multiple of 32 (SEER_ERR_UNSUPPORTED otherwise).  Workspace:
+ * the matrix-core kernel (SEER_ERR_UNSUPPORTED otherwise).  Workspace:
  * seer_decode_workspace_bytes(B, q_len*Hq, Hkv, d, max_sel).
  */
 seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv /* host struct */,

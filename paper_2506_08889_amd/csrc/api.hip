@@ -134,7 +134,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   const int rows = g * q_len;
   if (d != seer::kHeadDim || g > seer::kMaxGroup || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
   // several new tokens share the MFMA tile with the heads of the group: 16 rows, MFMA kernel only
-  if (q_len > 1 && (rows > seer::kMaxRows || block_size % 32 != 0 || g_knob_impl == 1)) return SEER_ERR_UNSUPPORTED;
+  if (q_len > 1 && (rows > seer::kMaxRows || g_knob_impl == 1)) return SEER_ERR_UNSUPPORTED;
   if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
   if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
     return SEER_ERR_SHAPE;
@@ -177,7 +177,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   p.out_is_f32 = out_dtype == SEER_F32;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  bool use_mfma = (block_size % 32 == 0);
+  bool use_mfma = true;
   if (g_knob_impl == 1) use_mfma = false;
   hipError_t e;
   {

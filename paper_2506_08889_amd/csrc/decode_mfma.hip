@@ -24,6 +24,9 @@
 //                 operand e covers features {8n+e}.  D then leaves lane (n,q) with
 //                 O[head n][32q .. 32q+31], contiguous.
 //
+// With 16-token blocks a 32-row step is fed by two list entries (rows 0-15 and 16-31), each with its
+// own address, valid count and position.
+//
 // Loads for the next half-block are issued as soon as the registers of the current one have
 // been consumed (K after its copy to LDS, V after the interleave), so each wave keeps 8-16 KiB
 // in flight.
@@ -40,6 +43,11 @@ struct HalfBlock {
   int64_t off;   // element offset of the first token of the half-block
   int ntok;      // valid tokens (1..32); 0 = no more work
   int tok0;      // position of its first token in the sequence
+  // 16-token blocks only: a step takes two list entries; rows 0..15 come from the first (fields above,
+  // ntok <= 16) and rows 16..31 from the second (fields below; ntok2 = 0 when the list has run out)
+  int64_t off2;
+  int ntok2;
+  int tok2;
 };
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) { return (x & 0xffffu) | (y << 16); }
@@ -60,7 +68,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }  // namespace
 
 // ROWS128: stride_token == 128 elements (rows back to back), so every row offset is an immediate.
-template <bool ROWS128>
+// B16: 16-token blocks, two list entries per 32-row step.
+template <bool ROWS128, bool B16>
 __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodeParams p) {
   // 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256 + 4 * kMaxRows * 2 * 4];
@@ -118,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   }
   const int end = (begin + p.blocks_per_split < n) ? begin + p.blocks_per_split : n;
   const int hpb = bs >> 5;                 // half-blocks (32 tokens) per block
-  const int nh = (end - begin) * hpb;      // half-blocks in this slice
+  const int nh = B16 ? (end - begin + 1) >> 1 : (end - begin) * hpb;      // 32-row steps in this slice
   const int64_t st = ROWS128 ? (int64_t)kHeadDim : p.stride_token;
   pf_stage2();
 
@@ -165,8 +174,11 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     r.off = 0;
     r.ntok = 0;
     r.tok0 = 0;
+    r.off2 = 0;
+    r.ntok2 = 0;
+    r.tok2 = 0;
     while (hb < nh) {
-      const int e = hb / hpb, half = hb - e * hpb;
+      const int e = B16 ? 2 * hb : hb / hpb, half = B16 ? 0 : hb - e * hpb;
       const int chunk = e >> 6;
       if (chunk != loaded_chunk) {
         finalize_chunk(chunk);
@@ -180,6 +192,26 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
       const int hi = __shfl((int)(uint32_t)((uint64_t)d_off >> 32), src);
       const int tk = __shfl(d_tok, src);
       hb += 4;
+      if (B16) {                               // the entry's partner sits in the next lane (e is even)
+        const int nt2 = __shfl(d_ntok, src + 1);
+        const int lo2 = __shfl((int)(uint32_t)(uint64_t)d_off, src + 1);
+        const int hi2 = __shfl((int)(uint32_t)((uint64_t)d_off >> 32), src + 1);
+        const int tk2 = __shfl(d_tok, src + 1);
+        if (nt_blk > 0 || nt2 > 0) {
+          r.off = (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+          r.ntok = nt_blk;
+          r.tok0 = tk;
+          r.off2 = (int64_t)(((uint64_t)(uint32_t)hi2 << 32) | (uint32_t)lo2);
+          r.ntok2 = nt2;
+          r.tok2 = tk2;
+          if (r.ntok == 0) {                   // keep "ntok > 0 means work": an invalid first entry swaps out
+            r.off = r.off2; r.ntok = r.ntok2; r.tok0 = r.tok2;
+            r.ntok2 = 0;
+          }
+          return r;
+        }
+        continue;
+      }
       int nt = nt_blk - half * 32;
       nt = nt > 32 ? 32 : nt;
       if (nt > 0) {
@@ -196,6 +228,17 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   // k-slot j of this lane's q: tau(q, j) = j < 4 ? 4q + j : 16 + 4q + (j - 4).
   uint4 kr[8], vr[8];
   auto load_k = [&](const HalfBlock& b) {
+    if (B16) {                                 // rows 0..15 from the first block, 16..31 from the second
+      const uint16_t* b0 = p.k + b.off + n16 * 8;
+      const uint16_t* b1 = p.k + b.off2 + n16 * 8;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int rr = 4 * (u & 3) + q4;
+        kr[u] = make_uint4(0, 0, 0, 0);
+        if (rr < (u < 4 ? b.ntok : b.ntok2)) kr[u] = load_stream16((u < 4 ? b0 : b1) + (int64_t)rr * st);
+      }
+      return;
+    }
     const uint16_t* base = p.k + b.off + n16 * 8;
     if (b.ntok == 32) {
 #pragma unroll
@@ -209,6 +252,17 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     }
   };
   auto load_v = [&](const HalfBlock& b) {
+    if (B16) {
+      const uint16_t* b0 = p.v + b.off + n16 * 8;
+      const uint16_t* b1 = p.v + b.off2 + n16 * 8;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int rr = 4 * q4 + (j & 3);       // slot j < 4: row 4*q4 + j of the first block, else of the second
+        vr[j] = make_uint4(0, 0, 0, 0);
+        if (rr < (j < 4 ? b.ntok : b.ntok2)) vr[j] = load_stream16((j < 4 ? b0 : b1) + (int64_t)rr * st);
+      }
+      return;
+    }
     const uint16_t* base = p.v + b.off + n16 * 8;
     if (b.ntok == 32) {
 #pragma unroll
@@ -274,7 +328,18 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[4 * t + r] = sacc[t][r] * p.scale_log2e;
-    if (cur.ntok < 32 || cur.tok0 + 32 > causal_from) {
+    if (B16) {
+      if (cur.ntok < 16 || cur.ntok2 < 16 || cur.tok0 + 16 > causal_from || cur.tok2 + 16 > causal_from) {
+        // tile t is block t of the pair: its own valid count and its own place in the sequence
+        const int lim0 = (cur.ntok < row_limit - cur.tok0) ? cur.ntok : row_limit - cur.tok0;
+        const int lim1 = (cur.ntok2 < row_limit - cur.tok2) ? cur.ntok2 : row_limit - cur.tok2;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (4 * q4 + r >= (t == 0 ? lim0 : lim1)) x[4 * t + r] = -INFINITY;
+      }
+    } else if (cur.ntok < 32 || cur.tok0 + 32 > causal_from) {
       // ragged tail of the sequence and / or the causal limit of this row among the new tokens
       const int lim = (cur.ntok < row_limit - cur.tok0) ? cur.ntok : row_limit - cur.tok0;
 #pragma unroll
@@ -375,10 +440,14 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s) {
   const dim3 grid = decode_grid(p);
-  if (p.stride_token == kHeadDim)
-    hipLaunchKernelGGL(seer_decode_split_mfma_kernel<true>, grid, dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL(seer_decode_split_mfma_kernel<false>, grid, dim3(256), 0, s, p);
+  const bool rows128 = p.stride_token == kHeadDim;
+  if (p.block_size == 16) {
+    if (rows128) hipLaunchKernelGGL((seer_decode_split_mfma_kernel<true, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((seer_decode_split_mfma_kernel<false, true>), grid, dim3(256), 0, s, p);
+  } else {
+    if (rows128) hipLaunchKernelGGL((seer_decode_split_mfma_kernel<true, false>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((seer_decode_split_mfma_kernel<false, false>), grid, dim3(256), 0, s, p);
+  }
   return hipGetLastError();
 }
 
