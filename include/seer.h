@@ -244,7 +244,7 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope /* host struct */, const
  *
  * q bf16 [B,T,Hq,d] contiguous; kv: contiguous addressing only (page_table must be NULL), at least
  * T tokens per sequence; out [B,T,Hq,d] of out_dtype; lse fp32 [B,T,Hq] (may be NULL);
- * gt fp32 [B,Hkv,T,ceil(T/block_size)].  block_size in {32, 64, 128}, d = 128, g in 1..8, scale > 0
+ * gt fp32 [B,Hkv,T,ceil(T/block_size)].  block_size in {16, 32, 64, 128}, d = 128, g in 1..8, scale > 0
  * (SEER_ERR_UNSUPPORTED otherwise).
  * Workspace: seer_attn_ground_truth_workspace_bytes.
  */

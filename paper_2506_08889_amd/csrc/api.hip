@@ -424,7 +424,7 @@ seer_status seer_attn_ground_truth_workspace_bytes(int B, int T, int Hq, int Hkv
   seer_status why;
   if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
   if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
-      (block_size != 32 && block_size != 64 && block_size != 128))
+      !block_size_ok(block_size))
     return SEER_ERR_UNSUPPORTED;
   *bytes = attn_gt_ws_bytes(B, T, Hq, block_size);
   return SEER_OK;
@@ -439,7 +439,7 @@ seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv, cons
   seer_status why;
   if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
   if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
-      (block_size != 32 && block_size != 64 && block_size != 128))
+      !block_size_ok(block_size))
     return SEER_ERR_UNSUPPORTED;
   if (kv->page_table) return SEER_ERR_UNSUPPORTED;      // whole-sequence training batches are contiguous
   if (!(scale > 0.f) || scale > 3.0e38f) return SEER_ERR_UNSUPPORTED;   // row maxima are taken before scaling

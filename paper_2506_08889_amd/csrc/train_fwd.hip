@@ -199,7 +199,16 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
           mh[c] = mx * p.scale_log2e;
         }
         // block maxima of the logits of this row (Sec. 2.3: the row maxima are reused)
-        if (p.block_size == 32) {
+        if (p.block_size == 16) {              // one block per 16-key tile: four maxima of 4 values + rows
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            float mx = fmaxf(fmaxf(x[4 * t], x[4 * t + 1]), fmaxf(x[4 * t + 2], x[4 * t + 3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const int j = (kt0 >> 4) + t;
+            if (q4 == 0 && qrow[a] < p.T && j < p.nb) rawbase[(int64_t)j * p.Tp + qrow[a]] = mx * p.scale_log2e;
+          }
+        } else if (p.block_size == 32) {
           if (q4 == 0 && qrow[a] < p.T) {
             const int j0 = kt0 >> 5;
             rawbase[(int64_t)j0 * p.Tp + qrow[a]] = mh[0];

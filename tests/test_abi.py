@@ -170,7 +170,7 @@ def test_training_forward_argument_errors_on_the_host():
         with pytest.raises(seer.SeerError) as e:
             seer.attn_ground_truth_workspace_bytes(*bad)
         assert e.value.status == -2
-    for bad in ((1, 64, 8, 2, 64, 64), (1, 64, 8, 2, 128, 16), (1, 64, 18, 2, 128, 64)):
+    for bad in ((1, 64, 8, 2, 64, 64), (1, 64, 8, 2, 128, 48), (1, 64, 18, 2, 128, 64)):
         with pytest.raises(seer.SeerError) as e:
             seer.attn_ground_truth_workspace_bytes(*bad)
         assert e.value.status == -3

@@ -75,6 +75,7 @@ def check(seer, q, k, v, b, scale, seqlens=None, out_dtype=torch.float32):
     (1, 333, 8, 1, 32),         # g = 8, blocks of one chunk
     (1, 517, 6, 2, 128),        # g = 3, blocks spanning two key tiles, several query tiles
     (2, 130, 5, 5, 64),         # g = 1
+    (2, 210, 4, 2, 16),         # the finest block size: one block per 16-key tile
     (1, 1024, 4, 1, 64),        # 8 query tiles x 16 key tiles
 ])
 def test_matches_oracle(seer, B, T, Hq, Hkv, b):
@@ -152,7 +153,7 @@ def test_randomised_shapes_lengths_and_layouts(seer):
         T = int(rng.choice([1, 31, 33, 63, 64, 65, 127, 128, 129, 191, 257, 300, 449]))
         Hkv = int(rng.choice([1, 2, 3]))
         g = int(rng.choice([1, 2, 4, 5, 8]))
-        b = int(rng.choice([32, 64, 128]))
+        b = int(rng.choice([16, 32, 64, 128]))
         spread = float(rng.choice([0.5, 1.0, 2.0]))
         strided = bool(rng.integers(0, 2))
         seed = 500 + case
