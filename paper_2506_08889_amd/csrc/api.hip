@@ -415,6 +415,8 @@ static size_t attn_gt_ws_bytes(int B, int T, int Hq, int block_size) {
 static bool attn_gt_sizes_ok(int B, int T, int Hq, int Hkv, seer_status* why) {
   if (B <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) { *why = SEER_ERR_SHAPE; return false; }
   if (B > 65535 || Hq > 65535) { *why = SEER_ERR_UNSUPPORTED; return false; }
+  // one work-group per (sequence, query head, 128-row tile) in a 1-D grid
+  if ((double)B * Hq * ((T + 127) / 128) > 2.0e9) { *why = SEER_ERR_UNSUPPORTED; return false; }
   return true;
 }
 

@@ -3,10 +3,11 @@
 // that the online softmax computes anyway are kept per (query row, key block) and turned into
 // probabilities once the row's log-sum-exp is known.
 //
-// Kernel 1, seer_attn_fwd_kernel: grid (query tiles of 128 rows, longest first; query head; sequence),
-// 256 threads.  A wave owns 32 query rows as two 16-row tiles and walks the keys 64 at a time (one
-// softmax step per 64 keys, two 32-key halves for the PV product).  The matrix-core formulation is the one of the decode kernel, with query rows in
-// the place of the heads of a group (lane = 16*q + n):
+// Kernel 1, seer_attn_fwd_kernel: one work-group of 256 threads per (sequence, query head, tile of 128
+// query rows), ordered so that the heads of a GQA group share an XCD's L2.  A wave owns 32 query rows
+// as two 16-row tiles and walks the keys 64 at a time (one softmax step per 64 keys, two 32-key halves
+// for the PV product).  The matrix-core formulation is the one of the decode kernel, with query rows
+// in the place of the heads of a group (lane = 16*q + n):
 //   S^T = K Q^T   A = 16 keys x 32 features from the work-group's K tile in LDS (XOR-swizzled rows,
 //                 double-buffered: the next tile is fetched into registers during the current one
 //                 and stored before the single barrier of the iteration); B = Q^T in registers.
@@ -61,8 +62,17 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;      // the tiles with the most keys first
-  const int h = blockIdx.y, i = blockIdx.z, hk = h / p.g;
+  // Work-group id -> (sequence, kv head, query tile, head of the group).  Work-groups are dealt to the 8
+  // XCDs round-robin by id, and each XCD has its own L2: the g heads of a group that work on the same
+  // query tile read the same K/V tiles, so they are given ids 8 apart (same XCD, launched together)
+  // and their K/V stream is filled into that L2 once instead of g times.  Within a (sequence, kv
+  // head) the query tiles with the most keys come first.
+  const int nqt = (p.T + kQTile - 1) / kQTile;
+  const int id = blockIdx.x, x8 = id & 7, t8 = id >> 3;
+  const int hh = t8 % p.g, pair = (t8 / p.g) * 8 + x8;        // pair = (sequence, kv head, query tile)
+  if (pair >= p.B * p.Hkv * nqt) return;                        // padding of the last group of 8
+  const int qt = nqt - 1 - pair % nqt;
+  const int hk = (pair / nqt) % p.Hkv, i = pair / (nqt * p.Hkv), h = hk * p.g + hh;
   int S = p.T;
   if (p.seqlens) {
     S = p.seqlens[i];
@@ -411,7 +421,8 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
 }
 
 hipError_t launch_attn_fwd(const TrainFwdParams& p, hipStream_t s) {
-  const dim3 grid((p.T + kQTile - 1) / kQTile, p.Hq, p.B);
+  const long pairs = (long)p.B * p.Hkv * ((p.T + kQTile - 1) / kQTile);
+  const dim3 grid((unsigned)(((pairs + 7) / 8) * 8 * p.g));
   if (p.stride_token == kHeadDim)
     hipLaunchKernelGGL(seer_attn_fwd_kernel<true>, grid, dim3(256), 0, s, p);
   else
