@@ -63,16 +63,26 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
   // Work-group id -> (sequence, kv head, query tile, head of the group).  Work-groups are dealt to the 8
-  // XCDs round-robin by id, and each XCD has its own L2: the g heads of a group that work on the same
-  // query tile read the same K/V tiles, so they are given ids 8 apart (same XCD, launched together)
-  // and their K/V stream is filled into that L2 once instead of g times.  Within a (sequence, kv
-  // head) the query tiles with the most keys come first.
+  // XCDs round-robin by id, and each XCD has its own L2.  Work-groups that read the same K/V stream
+  // are therefore given ids that are equal mod 8: always the g heads of a group on the same query
+  // tile, and - when the (sequence, kv head) groups divide evenly over the XCDs - all query tiles of a
+  // group, so that its K/V is filled into one L2 only.  Query tiles with the most keys come first.
   const int nqt = (p.T + kQTile - 1) / kQTile;
+  const int G = p.B * p.Hkv;
   const int id = blockIdx.x, x8 = id & 7, t8 = id >> 3;
-  const int hh = t8 % p.g, pair = (t8 / p.g) * 8 + x8;        // pair = (sequence, kv head, query tile)
-  if (pair >= p.B * p.Hkv * nqt) return;                        // padding of the last group of 8
-  const int qt = nqt - 1 - pair % nqt;
-  const int hk = (pair / nqt) % p.Hkv, i = pair / (nqt * p.Hkv), h = hk * p.g + hh;
+  const int hh = t8 % p.g;
+  int grp, qt;
+  if ((G & 7) == 0) {                          // group = 8 * (slot / nqt) + XCD, tile = slot % nqt
+    const int slot = t8 / p.g;
+    grp = (slot / nqt) * 8 + x8;
+    qt = nqt - 1 - slot % nqt;
+  } else {                                     // (group, tile) pairs round-robin over the XCDs
+    const int pair = (t8 / p.g) * 8 + x8;
+    if (pair >= G * nqt) return;               // padding of the last set of 8
+    grp = pair / nqt;
+    qt = nqt - 1 - pair % nqt;
+  }
+  const int hk = grp % p.Hkv, i = grp / p.Hkv, h = hk * p.g + hh;
   int S = p.T;
   if (p.seqlens) {
     S = p.seqlens[i];
