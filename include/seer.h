@@ -270,7 +270,9 @@ seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void*
  *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
  *   SEER_KNOB_DECODE_RAGGED  0 = the lists of a call have about equal lengths (token budget on
  *                            long sequences; default), 1 = very different lengths (per-sequence
- *                            budgets, threshold mode, mixed sequence lengths): shorter slices
+ *                            budgets, threshold mode, mixed sequence lengths): shorter decode
+ *                            slices, and a gate score kernel that walks long caches with few
+ *                            work-groups (hint for seer_gate_select and the decode calls)
  *   SEER_KNOB_GATE_IMPL      0 = auto, 1 = score kernel + select kernel, 2 = one fused kernel
  *                            (when the cache has at most 8192 blocks per sequence)
  */

@@ -298,7 +298,7 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
   }
   {
     Timed t(SEER_KERNEL_GATE_SCORE, s);
-    e = seer::launch_gate_score(p, s);
+    e = seer::launch_gate_score(p, g_knob_ragged != 0, s);
   }
   if (e != hipSuccess) return SEER_ERR_HIP;
   {

@@ -69,6 +69,75 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
   }
 }
 
+// The same scores for batches whose sequences differ widely in length: at most 8 work-groups per
+// (sequence, kv head), each walking every 8th tile of 64 cache rows with the next tile requested before
+// the current one is reduced.  With one work-group per tile of the longest sequence most of them would
+// start past the end of their own cache (c5: 23 of 33 thousand) and only hold a slot while they find
+// that out; equal-length batches are faster with the one-tile work-groups above.
+__global__ __launch_bounds__(256) void seer_gate_score_walk_kernel(GateParams p) {
+  const int i = blockIdx.z, h = blockIdx.y;
+  int S = p.seqlens[i];
+  S = S < 0 ? 0 : S;
+  int nfull = S / p.block_size;
+  nfull = nfull < p.nb_max ? nfull : p.nb_max;
+  const int j_first = blockIdx.x * kScoreRowsPerWg;
+  if (j_first >= nfull) return;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int slot = lane >> 4, c = lane & 15;
+  const int64_t grp = (int64_t)i * p.Hkv + h;
+
+  const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
+  double qd[8];
+  {
+    const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      qd[2 * e] = (double)bf16_lo(w[e]);
+      qd[2 * e + 1] = (double)bf16_hi(w[e]);
+    }
+  }
+
+  const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head;
+  const int step = gridDim.x * kScoreRowsPerWg;       // the work-groups of a group interleave their tiles
+  const int r = wave * 16 + slot;                     // this lane's row within a tile, + 4 * it
+  uint4 kr[4], kn[4];
+  auto load_tile = [&](int j0, uint4 (&dst)[4]) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int j = j0 + r + it * 4;
+      dst[it] = make_uint4(0, 0, 0, 0);
+      if (j < nfull) dst[it] = load_stream16(base + (int64_t)j * p.kc_stride_block + c * 8);
+    }
+  };
+  load_tile(j_first, kr);
+  for (int j0 = j_first; j0 < nfull; j0 += step) {
+    const bool more = j0 + step < nfull;
+    if (more) load_tile(j0 + step, kn);               // the next tile is in flight during the reduction
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const uint32_t w[4] = {kr[it].x, kr[it].y, kr[it].z, kr[it].w};
+      double acc = 0.0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
+        acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
+      }
+      // sum over the 16 lanes that share a row
+      acc += __shfl_xor(acc, 1);
+      acc += __shfl_xor(acc, 2);
+      acc += __shfl_xor(acc, 4);
+      acc += __shfl_xor(acc, 8);
+      const int j = j0 + r + it * 4;
+      if (c == 0 && j < nfull) p.scores[grp * p.nb_max + j] = acc + 0.0;  // -0 -> +0
+    }
+    if (more) {
+#pragma unroll
+      for (int it = 0; it < 4; ++it) kr[it] = kn[it];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Select kernel: one work-group per (sequence, kv head).  The scores of the group are first
 // brought into LDS (up to kSelectLdsBlocks of them; longer caches are re-read from L2).
@@ -520,9 +589,13 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   if (tid == 0) p.nblk[grp] = n;
 }
 
-hipError_t launch_gate_score(const GateParams& p, hipStream_t s) {
-  dim3 grid((p.nb_max + kScoreRowsPerWg - 1) / kScoreRowsPerWg, p.Hkv, p.B);
-  hipLaunchKernelGGL(seer_gate_score_kernel, grid, dim3(256), 0, s, p);
+hipError_t launch_gate_score(const GateParams& p, bool ragged, hipStream_t s) {
+  const int tiles = (p.nb_max + kScoreRowsPerWg - 1) / kScoreRowsPerWg;
+  if (ragged && tiles > 8) {
+    hipLaunchKernelGGL(seer_gate_score_walk_kernel, dim3(8, p.Hkv, p.B), dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL(seer_gate_score_kernel, dim3(tiles, p.Hkv, p.B), dim3(256), 0, s, p);
+  }
   return hipGetLastError();
 }
 

@@ -99,7 +99,7 @@ hipError_t launch_attn_fwd(const TrainFwdParams& p, hipStream_t s);
 hipError_t launch_gt_finalize(const TrainFwdParams& p, hipStream_t s);
 hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s);
 hipError_t launch_kc_update(const FrontKParams& p, int max_blocks, int cus, hipStream_t s);
-hipError_t launch_gate_score(const GateParams& p, hipStream_t s);
+hipError_t launch_gate_score(const GateParams& p, bool ragged, hipStream_t s);
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s);
 bool gate_fused_possible(const GateParams& p);
 hipError_t launch_gate_fused(const GateParams& p, hipStream_t s);

@@ -631,3 +631,27 @@ def test_bursts_and_overlapping_streams():
     torch.cuda.synchronize()
     for r in range(2):
         assert torch.equal(o[r], want[r][0]) and torch.equal(l[r], want[r][1]), "overlapping streams changed a result"
+
+
+def test_gate_score_walking_kernel_on_long_caches_of_mixed_length():
+    """With the mixed-lengths hint and caches longer than 8 tiles of 64 blocks the scores come from the
+    kernel that walks the cache with 8 work-groups per group: lengths from a few blocks to 3000,
+    a sequence ending exactly on a tile edge, block indices bit-exact in the hinted and unhinted mode."""
+    w = synth.Workload("walk", B=6, Hq=8, Hkv=2, block_size=64, seqlen_range=(64, 64 * 3000), seqlen_dist="uniform",
+                       budget_tokens=0, budget_frac=0.07, seed=909)
+    inp = synth.make_inputs(w, DEV)
+    sl = inp.seqlens_cpu.clone()
+    sl[0] = 64 * 512            # ends on the boundary of the 8th tile
+    sl[1] = 64 * 3 + 5          # a handful of blocks
+    sl[2] = int(inp.seqlens_cpu.max())
+    inp.seqlens_cpu = sl
+    inp.seqlens = sl.to(DEV)
+    assert inp.nb_max > 512
+    ref_idx, ref_cnt = oracle_gate(inp)
+    for hint in (1, 0):
+        seer.set_knob(2, hint)
+        seer.set_knob(3, 1)     # score kernel + select kernel
+        idx, cnt = seer.gate_select(inp.q_gate, inp.kc, inp.seqlens, w.block_size, budget_blocks=inp.budget_blocks,
+                                    max_sel=inp.max_sel)
+        torch.cuda.synchronize()
+        check_indices(idx, cnt, ref_idx, ref_cnt, what=f"walk hint={hint}")
