@@ -173,3 +173,37 @@ def test_randomised_shapes_lengths_and_layouts(seer):
         if spread > 1.0 and out_dtype == torch.bfloat16:
             out_dtype = torch.float32          # the 1e-2 bf16 bar is stated for unit-variance logits
         check(seer, q, k, v, b, 1.0 / math.sqrt(D), seqlens=sl, out_dtype=out_dtype)
+
+
+def test_hip_graph_capture_and_replay_match_eager(seer):
+    """The call allocates nothing, never synchronises and records no memset: captured into a HIP graph,
+    every replay reproduces the eager result bit for bit, with eager work between the replays."""
+    q, k, v = make(8, 2, 300, 4, 2)
+    B, Tn, Hq, Hkv, b = 2, 300, 4, 2, 64
+    nb = (Tn + b - 1) // b
+    out = torch.empty(B, Tn, Hq, D, dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty(B, Tn, Hq, dtype=torch.float32, device=DEV)
+    gt = torch.empty(B, Hkv, Tn, nb, dtype=torch.float32, device=DEV)
+    ws = torch.empty(seer.attn_ground_truth_workspace_bytes(B, Tn, Hq, Hkv, D, b), dtype=torch.uint8, device=DEV)
+
+    def step():
+        seer.attn_ground_truth(q, k, v, b, 0.09, out=out, lse=lse, gt=gt, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = (out.clone(), lse.clone(), gt.clone())
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (out, lse, gt):
+            t.zero_()
+        ws.random_(0, 255)                        # stale workspace contents must not matter
+        (q.float() * 2).sum().item()              # unrelated eager work + a synchronisation
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((out, lse, gt), ref):
+            assert torch.equal(got, want), f"replay {rep} differs from the eager result"
