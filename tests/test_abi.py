@@ -193,3 +193,14 @@ def test_training_forward_argument_errors_on_the_host():
     paged.stride_seq, paged.stride_head, paged.stride_token = 2 * 64 * 128, 64 * 128, 128
     paged.page_table, paged.max_pages, paged.page_size = 4096, 1, 64
     assert call(layout=paged) == -3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU; asked for more it exits with a message that says so (no GPU needed)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus must be 1" in r.stderr
