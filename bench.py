@@ -71,7 +71,8 @@ def main():
     ap.add_argument("--dense-steps", type=int, default=5, help="timed dense flash-decode steps (0 = skip the dense baseline)")
     ap.add_argument("--train-tokens", type=int, default=16384,
                     help="sequence length of the training-side forward (ground-truth kernel) leg, 0 = skip")
-    ap.add_argument("--also", default="c2", help="second workload reported compactly in the same line ('' = none)")
+    ap.add_argument("--also", default="c2,c5",
+                    help="further workloads reported compactly in the same line, comma-separated ('' = none)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (every box has one); --gpus must be 1. "
@@ -86,11 +87,12 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     seer.load_library()
     result = run_workload(args, args.workload, seer, synth, torch, np, full=True)
-    if args.also and args.also != args.workload:
-        time.sleep(3)      # let the GPU settle after the dense runs of the main workload
-        sec = run_workload(args, args.also, seer, synth, torch, np, full=False)
-        result["also"] = {args.also: {k: sec[k] for k in ("value", "unit", "ms_per_step", "config", "roofline",
-                                                           "kernels_avg_us", "dense", "speedup_vs_dense")}}
+    for name in [n for n in args.also.split(",") if n and n != args.workload]:
+        time.sleep(3)      # let the GPU settle after the dense runs of the previous workload
+        torch.cuda.empty_cache()
+        sec = run_workload(args, name, seer, synth, torch, np, full=False)
+        result.setdefault("also", {})[name] = {k: sec[k] for k in ("value", "unit", "ms_per_step", "config", "roofline",
+                                                                     "kernels_avg_us", "dense", "speedup_vs_dense")}
     print(json.dumps(result), flush=True)
 
 
