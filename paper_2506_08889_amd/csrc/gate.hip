@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   }
   if (SRC == 2) {
     // Stream the group's cache rows: 16 lanes per 256-byte row, 4 rows per wave and load, 8 loads
-    // (32 KiB per work-group) in flight.
+    // (32 KiB per work-group) per step, the next step's loads issued before the current reduction.
     double* sl = reinterpret_cast<double*>(dyn_smem);
     const int slot = lane >> 4, c = lane & 15;
     const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
@@ -270,14 +270,19 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
       }
     }
     const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + c * 8;
-    for (int j0 = 0; j0 < nfull; j0 += 128) {
-      uint4 kr[8];
+    uint4 kr[8], kn[8];
+    auto load_rows = [&](int j0, uint4 (&dst)[8]) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int j = j0 + u * 16 + wave * 4 + slot;
-        kr[u] = make_uint4(0, 0, 0, 0);
-        if (j < nfull) kr[u] = load_stream16(base + (int64_t)j * p.kc_stride_block);
+        dst[u] = make_uint4(0, 0, 0, 0);
+        if (j < nfull) dst[u] = load_stream16(base + (int64_t)j * p.kc_stride_block);
       }
+    };
+    load_rows(0, kr);
+    for (int j0 = 0; j0 < nfull; j0 += 128) {
+      const bool more = j0 + 128 < nfull;
+      if (more) load_rows(j0 + 128, kn);         // the next 128 rows are in flight during the reduction
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int j = j0 + u * 16 + wave * 4 + slot;
@@ -293,6 +298,10 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
         acc += __shfl_xor(acc, 4);
         acc += __shfl_xor(acc, 8);
         if (c == 0 && j < nfull) sl[j] = acc + 0.0;   // -0 -> +0
+      }
+      if (more) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) kr[u] = kn[u];
       }
     }
     __syncthreads();
