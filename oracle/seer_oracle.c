@@ -161,7 +161,10 @@ int oracle_gate_select(const uint16_t* q_gate, const uint16_t* kc_cache, int64_t
       } else {
         /* top-p (nucleus) selection, named as the way to adaptive sparsity in Sec. 6.2: walk the
          * blocks from the highest score down (equal scores: lower index first) and keep them until
-         * their accumulated gate probability reaches p; at least one block is kept. */
+         * their accumulated gate probability reaches p; at least one block is kept.  p >= 1 asks
+         * for the whole mass: every softmax probability is positive, so in exact arithmetic only
+         * the set of all full blocks has it - that case is decided here and not left to whether a
+         * rounded running sum happens to touch 1.0 before the last block. */
         if (nfull > 0) {
           const double inv = 1.0 / sqrt((double)Dg);
           double m = -INFINITY;
@@ -175,7 +178,7 @@ int oracle_gate_select(const uint16_t* q_gate, const uint16_t* kc_cache, int64_t
           for (int r = 0; r < nfull; ++r) {
             sel[n++] = order[r].j;
             cum += exp(order[r].s * inv - m) / Z;
-            if (cum >= threshold) break;
+            if (threshold < 1.0 && cum >= threshold) break;
           }
           free(order);
         }

@@ -478,6 +478,17 @@ def test_top_p_mode_matches_sorted_cumulative_probabilities():
     idx, cnt = oracle.gate_select(qg, kc8, torch.tensor([8 * b, 8 * b], dtype=torch.int32), b, mode=oracle.SELECT_TOPP,
                                   threshold=0.5, max_sel=8)
     assert (cnt == 4).all() and idx[0, 0, :4].tolist() == [0, 1, 2, 3]
+    # p = 1 is the whole mass, i.e. every full block, also when one block dominates so strongly that a
+    # rounded running sum touches 1.0 after the first block (5 blocks: scores 512, 0, 0, 0, 0 -> the
+    # first probability is 1 - 4e-20, which is 1.0 in fp64); just below 1 the nucleus is that one block
+    qd = torch.zeros(1, 1, 128, dtype=torch.bfloat16); qd[0, 0, 0] = 32.0
+    kd = torch.zeros(1, 1, 6, 128, dtype=torch.bfloat16); kd[0, 0, 0, 0] = 16.0
+    kd[0, 0, 5] = 99.0                                                 # stale entry of the partial sixth block: never read
+    sl5 = torch.tensor([5 * b + 7], dtype=torch.int32)
+    idx, cnt = oracle.gate_select(qd, kd, sl5, b, mode=oracle.SELECT_TOPP, threshold=1.0, max_sel=6)
+    assert cnt.tolist() == [[6]] and idx[0, 0].tolist() == [0, 1, 2, 3, 4, 5]
+    idx, cnt = oracle.gate_select(qd, kd, sl5, b, mode=oracle.SELECT_TOPP, threshold=0.999999, max_sel=6)
+    assert cnt.tolist() == [[2]] and idx[0, 0, :2].tolist() == [0, 5]
 
 
 def test_multi_token_decode_is_a_stack_of_single_token_decodes_and_causal():
