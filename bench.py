@@ -102,7 +102,6 @@ def run_workload(args, workload, seer, synth, torch, np, full):
     seer.set_knob(1, args.splits)
     w = synth.CONFIGS[workload]
     ragged = w.seqlen_dist != "fixed" or w.budget_tokens == 0      # lists of very different lengths
-    seer.set_knob(2, 1 if ragged else 0)
     seer.set_knob(3, args.gate_impl)
     log(f"[bench] workload {w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} bs={w.block_size} paged={w.paged}")
 
@@ -139,14 +138,14 @@ def run_workload(args, workload, seer, synth, torch, np, full):
         k, v = caches[i % kv_copies]
         seer.gate_select(qgs[r], base.kc, base.seqlens, bs, budget_tokens=w.budget_tokens,
                          budget_blocks=base.budget_blocks, max_sel=max_sel, block_idx=idxs[r], nblk=cnts[r],
-                         workspace=ws_gate)
+                         workspace=ws_gate, ragged=ragged)
         seer.sparse_decode(qs[r], k, v, base.seqlens, idxs[r], cnts[r], bs, w.scale, page_table=base.page_table,
-                           page_size=base.page_size, out=out, lse=lse, workspace=ws_dec)
+                           page_size=base.page_size, out=out, lse=lse, workspace=ws_dec, ragged=ragged)
 
     def dense_step(i):
         k, v = caches[i % kv_copies]
         seer.dense_decode(qs[i % R], k, v, base.seqlens, base.nb_max, bs, w.scale, page_table=base.page_table,
-                          page_size=base.page_size, out=out, lse=lse, workspace=ws_dense)
+                          page_size=base.page_size, out=out, lse=lse, workspace=ws_dense, ragged=ragged)
 
     def timed(fn, n, start=0):
         torch.cuda.synchronize()
@@ -265,7 +264,7 @@ def run_workload(args, workload, seer, synth, torch, np, full):
             k_, v_ = caches[i % kv_copies]
             seer.sparse_decode_multi(qm, k_, v_, base.seqlens, idxs[i % R], cnts[i % R], bs, w.scale,
                                      page_table=base.page_table, page_size=base.page_size, out=out_m, lse=lse_m,
-                                     workspace=ws_m)
+                                     workspace=ws_m, ragged=ragged)
 
         for i in range(3):
             mt(i)
@@ -326,9 +325,10 @@ def run_workload(args, workload, seer, synth, torch, np, full):
 
     # ---- byte model from the selection the gate actually made (query set 0)
     seer.gate_select(qgs[0], base.kc, base.seqlens, bs, budget_tokens=w.budget_tokens, budget_blocks=base.budget_blocks,
-                     max_sel=max_sel, block_idx=idxs[0], nblk=cnts[0], workspace=ws_gate)
+                     max_sel=max_sel, block_idx=idxs[0], nblk=cnts[0], workspace=ws_gate, ragged=ragged)
     seer.sparse_decode(qs[0], caches[0][0], caches[0][1], base.seqlens, idxs[0], cnts[0], bs, w.scale,
-                       page_table=base.page_table, page_size=base.page_size, out=out, lse=lse, workspace=ws_dec)
+                       page_table=base.page_table, page_size=base.page_size, out=out, lse=lse, workspace=ws_dec,
+                       ragged=ragged)
     torch.cuda.synchronize()
     idx_cpu, cnt_cpu = idxs[0].cpu(), cnts[0].cpu()
     ab = algorithmic_bytes(w, base.seqlens_cpu, cnt_cpu, idx_cpu, max_sel)

@@ -60,6 +60,19 @@ typedef enum seer_select_mode {
 typedef enum seer_dtype { SEER_BF16 = 0, SEER_F32 = 1 } seer_dtype;
 
 /*
+ * What the caller knows about the block lists of ONE call (bit set, passed as `hints`; 0 = nothing).
+ * A hint never changes a result, only the launch plan.
+ *   SEER_HINT_RAGGED_LISTS  the lists of this call differ widely in length (per-sequence budgets,
+ *                           threshold or top-p selection, mixed sequence lengths): the decode calls
+ *                           cut the lists into slices of about 2048 tokens so that the longest list
+ *                           spreads over many work-groups, and seer_gate_select walks long caches
+ *                           with few work-groups per sequence.  Lists of about equal length (one
+ *                           token budget on long sequences) are ~5 % faster without it.
+ * Unknown bits are refused (SEER_ERR_UNSUPPORTED).
+ */
+typedef enum seer_hint { SEER_HINT_NONE = 0, SEER_HINT_RAGGED_LISTS = 1 } seer_hint;
+
+/*
  * Addressing of the bf16 KV cache.  Element (sequence i, kv head h, token t, feature c):
  *   contiguous (page_table == NULL):  i*stride_seq + h*stride_head + t*stride_token + c
  *   paged:  page = page_table[i*max_pages + t/page_size];
@@ -96,13 +109,13 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
                                         size_t* bytes /* host, out */);
 
 /*
- * How the decode calls will cut the block lists for these sizes under the current knobs (host call,
- * no device work): num_splits slices of blocks_per_split list entries each, the partition along
- * num_split of Sec. 3.3.  num_splits * blocks_per_split >= max_blocks; num_splits == 1 means no
- * merge kernel is launched.
+ * How the decode calls will cut the block lists for these sizes and hints (host call, no device
+ * work): num_splits slices of blocks_per_split list entries each, the partition along num_split of
+ * Sec. 3.3.  num_splits * blocks_per_split >= max_blocks; num_splits == 1 means no merge kernel is
+ * launched.
  */
-seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, int* num_splits /* host, out */,
-                             int* blocks_per_split /* host, out */);
+seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, uint32_t hints,
+                             int* num_splits /* host, out */, int* blocks_per_split /* host, out */);
 
 /*
  * AttnGate block selection (Eq. 1c; Sec. 3.1; Sec. 3.2).
@@ -140,7 +153,7 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
                              const int32_t* budget_blocks, double threshold,
                              int32_t* block_idx /* out [B,Hkv,max_sel] */,
                              int32_t* nblk /* out [B,Hkv] */, int max_sel, void* workspace,
-                             size_t workspace_bytes, void* stream);
+                             size_t workspace_bytes, uint32_t hints, void* stream);
 
 /*
  * Block-sparse flash-decoding (Sec. 3.3).
@@ -159,7 +172,8 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv /* host s
                                const int32_t* seqlens, const int32_t* block_idx,
                                const int32_t* nblk, int max_sel, int B, int Hq, int Hkv, int d,
                                int block_size, float scale, void* out, seer_dtype out_dtype,
-                               float* lse, void* workspace, size_t workspace_bytes, void* stream);
+                               float* lse, void* workspace, size_t workspace_bytes, uint32_t hints,
+                               void* stream);
 
 /*
  * Several new tokens per sequence in one call - the multi-token / speculative decoding direction of
@@ -178,7 +192,7 @@ seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv /* 
                                      const int32_t* seqlens, const int32_t* block_idx, const int32_t* nblk,
                                      int max_sel, int B, int q_len, int Hq, int Hkv, int d, int block_size,
                                      float scale, void* out, seer_dtype out_dtype, float* lse,
-                                     void* workspace, size_t workspace_bytes, void* stream);
+                                     void* workspace, size_t workspace_bytes, uint32_t hints, void* stream);
 
 /*
  * Dense flash-decode over all ceil(seqlens[i]/block_size) blocks of every sequence: the
@@ -188,7 +202,8 @@ seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv /* 
 seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv /* host struct */,
                               const int32_t* seqlens, int max_blocks, int B, int Hq, int Hkv, int d,
                               int block_size, float scale, void* out, seer_dtype out_dtype,
-                              float* lse, void* workspace, size_t workspace_bytes, void* stream);
+                              float* lse, void* workspace, size_t workspace_bytes, uint32_t hints,
+                              void* stream);
 
 /*
  * AttnGate front-end, Q branch (Eq. 1a): per (sequence i, kv head h) the g pre-RoPE query heads
@@ -265,21 +280,19 @@ seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv /* ho
 seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void* stream);
 
 /*
- * Tuning knobs (process-wide, host call).  Unknown knobs return SEER_ERR_UNSUPPORTED.
+ * Measurement and test knobs (process-wide, host call; each is one atomic integer that a call reads
+ * once, so setting one while calls run on other threads is safe but affects whichever calls read it
+ * afterwards).  They force a kernel variant or a split count so that every variant can be measured
+ * and tested; production callers leave them at 0 and describe their lists through `hints`.
+ * Unknown knobs return SEER_ERR_UNSUPPORTED.
  *   SEER_KNOB_DECODE_IMPL    0 = auto, 1 = VALU kernel, 2 = MFMA kernel
  *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
- *   SEER_KNOB_DECODE_RAGGED  0 = the lists of a call have about equal lengths (token budget on
- *                            long sequences; default), 1 = very different lengths (per-sequence
- *                            budgets, threshold mode, mixed sequence lengths): shorter decode
- *                            slices, and a gate score kernel that walks long caches with few
- *                            work-groups (hint for seer_gate_select and the decode calls)
  *   SEER_KNOB_GATE_IMPL      0 = auto, 1 = score kernel + select kernel, 2 = one fused kernel
  *                            (when the cache has at most 8192 blocks per sequence)
  */
 typedef enum seer_knob {
   SEER_KNOB_DECODE_IMPL = 0,
   SEER_KNOB_DECODE_SPLITS = 1,
-  SEER_KNOB_DECODE_RAGGED = 2,
   SEER_KNOB_GATE_IMPL = 3
 } seer_knob;
 seer_status seer_set_knob(int knob, int value);
@@ -287,9 +300,10 @@ seer_status seer_get_knob(int knob, int* value /* host, out */);
 
 /*
  * Per-kernel timing for the bench.  While enabled, each kernel launch of the calls above is
- * bracketed by HIP events on the caller's stream.  seer_profile_read synchronises on the
- * recorded events and returns, for the kernel class `which`, the number of launches seen
- * since the last reset and their total duration in milliseconds.
+ * bracketed by HIP events on the caller's stream.  seer_profile_durations synchronises on the
+ * recorded events and returns, for the kernel class `which`, the number of launches seen since the
+ * last reset and, in launch order, the duration in milliseconds of the first `capacity` of them
+ * (ms may be NULL when capacity is 0); the caller forms the mean, median and minimum.
  */
 typedef enum seer_kernel_class {
   SEER_KERNEL_GATE_SCORE = 0,
@@ -305,7 +319,8 @@ typedef enum seer_kernel_class {
 } seer_kernel_class;
 seer_status seer_profile_enable(int on);
 seer_status seer_profile_reset(void);
-seer_status seer_profile_read(int which, int* launches /* host, out */, double* total_ms /* host, out */);
+seer_status seer_profile_durations(int which, double* ms /* host, out [capacity] */, int capacity,
+                                   int* launches /* host, out */);
 
 #ifdef __cplusplus
 }

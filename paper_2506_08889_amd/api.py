@@ -17,9 +17,9 @@ _lib = None
 SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
 SELECT_TOPP = 2
+HINT_RAGGED_LISTS = 1
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
-KNOB_DECODE_RAGGED = 2
 KNOB_GATE_IMPL = 3
 KERNEL_CLASSES = ("gate_score", "gate_select", "decode_split", "decode_merge", "stream_read", "gate_q", "kc_update",
                   "attn_fwd", "gt_finalize")
@@ -58,7 +58,7 @@ def load_library():
         from . import build as _build
         _build.build()
     lib = ctypes.CDLL(path)
-    c_int, c_i64, c_vp, c_sz = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    c_int, c_i64, c_vp, c_sz, c_u32 = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32
     lib.seer_version.restype = c_int
     lib.seer_status_string.restype = ctypes.c_char_p
     lib.seer_status_string.argtypes = [c_int]
@@ -67,22 +67,22 @@ def load_library():
     lib.seer_decode_workspace_bytes.restype = c_int
     lib.seer_decode_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, ctypes.POINTER(c_sz)]
     lib.seer_decode_plan.restype = c_int
-    lib.seer_decode_plan.argtypes = [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int), ctypes.POINTER(c_int)]
+    lib.seer_decode_plan.argtypes = [c_int, c_int, c_int, c_int, c_u32, ctypes.POINTER(c_int), ctypes.POINTER(c_int)]
     lib.seer_gate_select.restype = c_int
     lib.seer_gate_select.argtypes = [c_vp, c_vp, c_i64, c_i64, c_i64, c_vp, c_int, c_int, c_int, c_int,
                                      c_int, c_int, ctypes.c_int32, c_vp, ctypes.c_double, c_vp, c_vp,
-                                     c_int, c_vp, c_sz, c_vp]
+                                     c_int, c_vp, c_sz, c_u32, c_vp]
     lib.seer_sparse_decode.restype = c_int
     lib.seer_sparse_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int,
                                        c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
-                                       c_vp, c_sz, c_vp]
+                                       c_vp, c_sz, c_u32, c_vp]
     lib.seer_sparse_decode_multi.restype = c_int
     lib.seer_sparse_decode_multi.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int, c_int,
                                              c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
-                                             c_vp, c_sz, c_vp]
+                                             c_vp, c_sz, c_u32, c_vp]
     lib.seer_dense_decode.restype = c_int
     lib.seer_dense_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_int, c_int, c_int, c_int,
-                                      c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_vp]
+                                      c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_u32, c_vp]
     lib.seer_gate_q.restype = c_int
     lib.seer_gate_q.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.seer_kc_update.restype = c_int
@@ -102,8 +102,8 @@ def load_library():
     lib.seer_profile_enable.restype = c_int
     lib.seer_profile_enable.argtypes = [c_int]
     lib.seer_profile_reset.restype = c_int
-    lib.seer_profile_read.restype = c_int
-    lib.seer_profile_read.argtypes = [c_int, ctypes.POINTER(c_int), ctypes.POINTER(ctypes.c_double)]
+    lib.seer_profile_durations.restype = c_int
+    lib.seer_profile_durations.argtypes = [c_int, ctypes.POINTER(ctypes.c_double), c_int, ctypes.POINTER(c_int)]
     _lib = lib
     return lib
 
@@ -145,11 +145,16 @@ def decode_workspace_bytes(B: int, Hq: int, Hkv: int, d: int, max_blocks: int) -
     return int(n.value)
 
 
-def decode_plan(B: int, Hkv: int, max_blocks: int, block_size: int):
+def _hints(ragged: bool) -> int:
+    return HINT_RAGGED_LISTS if ragged else 0
+
+
+def decode_plan(B: int, Hkv: int, max_blocks: int, block_size: int, ragged: bool = False):
     """seer_decode_plan: (num_splits, blocks_per_split) the decode calls will use for these sizes."""
     ns, per = ctypes.c_int(0), ctypes.c_int(0)
     _check("seer_decode_plan",
-           load_library().seer_decode_plan(B, Hkv, max_blocks, block_size, ctypes.byref(ns), ctypes.byref(per)))
+           load_library().seer_decode_plan(B, Hkv, max_blocks, block_size, _hints(ragged), ctypes.byref(ns),
+                                           ctypes.byref(per)))
     return int(ns.value), int(per.value)
 
 
@@ -160,7 +165,8 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 def gate_select(q_gate: torch.Tensor, kc_cache: torch.Tensor, seqlens: torch.Tensor, block_size: int, *,
                 mode: int = SELECT_TOPK, budget_tokens: int = 0, budget_blocks: Optional[torch.Tensor] = None,
                 threshold: float = 0.0, max_sel: int, block_idx: Optional[torch.Tensor] = None,
-                nblk: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+                nblk: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                ragged: bool = False):
     """seer_gate_select.  q_gate [B,Hkv,Dg] bf16, kc_cache [B,Hkv,nb_max,Dg] bf16 (last dim
     contiguous), seqlens [B] int32.  Returns (block_idx [B,Hkv,max_sel] int32, nblk [B,Hkv] int32)."""
     lib = load_library()
@@ -185,7 +191,7 @@ def gate_select(q_gate: torch.Tensor, kc_cache: torch.Tensor, seqlens: torch.Ten
     st = lib.seer_gate_select(_ptr(q_gate), _ptr(kc_cache), kc_cache.stride(0), kc_cache.stride(1),
                               kc_cache.stride(2), _ptr(seqlens), B, Hkv, Dg, nb_max, block_size, mode,
                               int(budget_tokens), _ptr(budget_blocks), float(threshold), _ptr(block_idx),
-                              _ptr(nblk), max_sel, _ptr(workspace), workspace.numel(), _stream())
+                              _ptr(nblk), max_sel, _ptr(workspace), workspace.numel(), _hints(ragged), _stream())
     _check("seer_gate_select", st)
     return block_idx, nblk
 
@@ -228,7 +234,7 @@ def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: to
                   block_idx: torch.Tensor, nblk: torch.Tensor, block_size: int, scale: float, *,
                   page_table: Optional[torch.Tensor] = None, page_size: int = 0,
                   out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                  out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+                  out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None, ragged: bool = False):
     """seer_sparse_decode.  q [B,Hq,d] bf16; k/v contiguous [B,Hkv,S,d] views or paged pools
     [n_pages,Hkv,page,d] with page_table [B,max_pages]; block_idx [B,Hkv,max_sel], nblk [B,Hkv]
     int32.  Returns (out [B,Hq,d], lse [B,Hq] fp32)."""
@@ -247,7 +253,7 @@ def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: to
     st = lib.seer_sparse_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
                                 max_sel, B, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
                                 0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
-                                workspace.numel(), _stream())
+                                workspace.numel(), _hints(ragged), _stream())
     _check("seer_sparse_decode", st)
     return out, lse
 
@@ -256,7 +262,7 @@ def sparse_decode_multi(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqle
                         block_idx: torch.Tensor, nblk: torch.Tensor, block_size: int, scale: float, *,
                         page_table: Optional[torch.Tensor] = None, page_size: int = 0,
                         out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                        out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+                        out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None, ragged: bool = False):
     """seer_sparse_decode_multi.  q [B,q_len,Hq,d] bf16 (the last q_len tokens of each sequence).
     Returns (out [B,q_len,Hq,d], lse [B,q_len,Hq] fp32)."""
     lib = load_library()
@@ -277,7 +283,7 @@ def sparse_decode_multi(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqle
     st = lib.seer_sparse_decode_multi(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
                                       max_sel, B, T, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
                                       0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
-                                      workspace.numel(), _stream())
+                                      workspace.numel(), _hints(ragged), _stream())
     _check("seer_sparse_decode_multi", st)
     return out, lse
 
@@ -332,7 +338,7 @@ def attn_ground_truth(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, block_s
 def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor, max_blocks: int,
                  block_size: int, scale: float, *, page_table: Optional[torch.Tensor] = None,
                  page_size: int = 0, out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                 out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None):
+                 out_dtype=torch.bfloat16, workspace: Optional[torch.Tensor] = None, ragged: bool = False):
     """seer_dense_decode: the same kernels over every block of every sequence."""
     lib = load_library()
     _want(q, torch.bfloat16, "q"); _want(seqlens, torch.int32, "seqlens")
@@ -347,7 +353,7 @@ def dense_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: tor
     st = lib.seer_dense_decode(_ptr(q), ctypes.byref(lay), _ptr(seqlens), max_blocks, B, Hq, Hkv, d,
                                block_size, ctypes.c_float(scale), _ptr(out),
                                0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
-                               workspace.numel(), _stream())
+                               workspace.numel(), _hints(ragged), _stream())
     _check("seer_dense_decode", st)
     return out, lse
 
@@ -436,9 +442,17 @@ def profile_reset():
     _check("seer_profile_reset", load_library().seer_profile_reset())
 
 
+def profile_durations(which: int):
+    """seer_profile_durations: the duration in ms of every launch of one kernel class since the last reset."""
+    lib = load_library()
+    n = ctypes.c_int(0)
+    _check("seer_profile_durations", lib.seer_profile_durations(which, None, 0, ctypes.byref(n)))
+    buf = (ctypes.c_double * max(n.value, 1))()
+    _check("seer_profile_durations", lib.seer_profile_durations(which, buf, n.value, ctypes.byref(n)))
+    return [float(buf[i]) for i in range(n.value)]
+
+
 def profile_read(which: int):
     """(launches, total_ms) of one kernel class since the last reset."""
-    n = ctypes.c_int(0)
-    ms = ctypes.c_double(0.0)
-    _check("seer_profile_read", load_library().seer_profile_read(which, ctypes.byref(n), ctypes.byref(ms)))
-    return int(n.value), float(ms.value)
+    d = profile_durations(which)
+    return len(d), float(sum(d))

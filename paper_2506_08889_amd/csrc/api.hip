@@ -5,6 +5,7 @@
 
 #include <math.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -12,10 +13,12 @@
 
 namespace {
 
-int g_knob_impl = 0;
-int g_knob_splits = 0;
-int g_knob_ragged = 0;
-int g_knob_gate = 0;
+// Measurement / test knobs (seer_set_knob).  Atomic so that a setter on one thread never tears a
+// reader on another; a call reads each knob once.  What a caller knows about its own lists travels
+// with the call (the `hints` argument), not through these.
+std::atomic<int> g_knob_impl{0};
+std::atomic<int> g_knob_splits{0};
+std::atomic<int> g_knob_gate{0};
 
 struct ProfEvent { int cls; hipEvent_t a, b; };
 bool g_prof_on = false;
@@ -46,7 +49,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // about 6.5 us, which a work-group needs to read about 8 blocks of 64 tokens by itself
 // (~0.8 us each), so short lists are only cut when the slices save more than the merge costs.
 // A slice has at least 4 list entries.
-// Lists of very different lengths (SEER_KNOB_DECODE_RAGGED) get slices of about 2048 tokens so
+// Lists of very different lengths (SEER_HINT_RAGGED_LISTS) get slices of about 2048 tokens so
 // that the longest list is spread over many work-groups; equal-length lists lose ~5 % to that,
 // hence the opt-in.
 constexpr long kMinSliceBlocks = 4;    // at least one block per wave of a work-group
@@ -57,13 +60,15 @@ long max_splits_for(int max_blocks) {
   return m < 1 ? 1 : (m > kMaxSplits ? kMaxSplits : m);
 }
 
-void plan_splits(int B, int Hkv, int max_blocks, int block_size, int* num_splits, int* blocks_per_split) {
+void plan_splits(int B, int Hkv, int max_blocks, int block_size, bool ragged, int* num_splits,
+                 int* blocks_per_split) {
   const long groups = (long)B * Hkv;
   const long slots = (long)cu_count();
   const long cap = max_splits_for(max_blocks);
+  const int forced = g_knob_splits.load(std::memory_order_relaxed);
   long ns;
-  if (g_knob_splits > 0) {
-    ns = g_knob_splits;
+  if (forced > 0) {
+    ns = forced;
   } else {
     ns = groups >= slots ? 1 : (slots + groups / 2) / groups;
     if (ns > cap) ns = cap;
@@ -72,7 +77,7 @@ void plan_splits(int B, int Hkv, int max_blocks, int block_size, int* num_splits
       const double saved = 0.8 * (block_size / 64.0) * max_blocks * (1.0 - 1.0 / (double)ns);
       if (saved < 6.5) ns = 1;
     }
-    if (g_knob_ragged) {
+    if (ragged) {
       long len_r = 2048 / block_size;
       if (len_r < kMinSliceBlocks) len_r = kMinSliceBlocks;
       const long ns_r = (max_blocks + len_r - 1) / len_r;
@@ -122,7 +127,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
                           const int32_t* block_idx, const int32_t* nblk, int max_blocks, bool sparse,
                           int B, int q_len, int Hq, int Hkv, int d, int block_size, float scale, void* out,
                           seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
-                          void* stream) {
+                          uint32_t hints, void* stream) {
   if (!q || !kv || !seqlens || !out) return SEER_ERR_NULL;
   if (!kv->k || !kv->v) return SEER_ERR_NULL;
   if (sparse && (!block_idx || !nblk)) return SEER_ERR_NULL;
@@ -130,11 +135,13 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
     return SEER_ERR_SHAPE;
   if (Hq % Hkv != 0) return SEER_ERR_SHAPE;
   if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
+  if (hints & ~(uint32_t)SEER_HINT_RAGGED_LISTS) return SEER_ERR_UNSUPPORTED;
   const int g = Hq / Hkv;
   const int rows = g * q_len;
+  const int impl = g_knob_impl.load(std::memory_order_relaxed);
   if (d != seer::kHeadDim || g > seer::kMaxGroup || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
   // several new tokens share the MFMA tile with the heads of the group: 16 rows, MFMA kernel only
-  if (q_len > 1 && (rows > seer::kMaxRows || g_knob_impl == 1)) return SEER_ERR_UNSUPPORTED;
+  if (q_len > 1 && (rows > seer::kMaxRows || impl == 1)) return SEER_ERR_UNSUPPORTED;
   if (out_dtype != SEER_BF16 && out_dtype != SEER_F32) return SEER_ERR_UNSUPPORTED;
   if (kv->stride_token < d || (kv->stride_token % 8) || (kv->stride_head % 8) || (kv->stride_seq % 8))
     return SEER_ERR_SHAPE;
@@ -143,7 +150,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
     if (kv->page_size <= 0 || kv->max_pages <= 0 || kv->page_size % block_size != 0) return SEER_ERR_SHAPE;
   }
   int ns, len;
-  plan_splits(B, Hkv, max_blocks, block_size, &ns, &len);
+  plan_splits(B, Hkv, max_blocks, block_size, (hints & SEER_HINT_RAGGED_LISTS) != 0, &ns, &len);
   const size_t need = decode_ws_bytes(B, Hkv, rows, max_splits_for(max_blocks));
   if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SEER_ERR_WORKSPACE;
@@ -177,8 +184,7 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   p.out_is_f32 = out_dtype == SEER_F32;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  bool use_mfma = true;
-  if (g_knob_impl == 1) use_mfma = false;
+  const bool use_mfma = impl != 1;
   hipError_t e;
   {
     Timed t(SEER_KERNEL_DECODE_SPLIT, s);
@@ -227,12 +233,12 @@ seer_status seer_decode_workspace_bytes(int B, int Hq, int Hkv, int d, int max_b
   return SEER_OK;
 }
 
-seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, int* num_splits,
+seer_status seer_decode_plan(int B, int Hkv, int max_blocks, int block_size, uint32_t hints, int* num_splits,
                              int* blocks_per_split) {
   if (!num_splits || !blocks_per_split) return SEER_ERR_NULL;
   if (B <= 0 || Hkv <= 0 || max_blocks <= 0) return SEER_ERR_SHAPE;
-  if (!block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
-  plan_splits(B, Hkv, max_blocks, block_size, num_splits, blocks_per_split);
+  if (!block_size_ok(block_size) || (hints & ~(uint32_t)SEER_HINT_RAGGED_LISTS)) return SEER_ERR_UNSUPPORTED;
+  plan_splits(B, Hkv, max_blocks, block_size, (hints & SEER_HINT_RAGGED_LISTS) != 0, num_splits, blocks_per_split);
   return SEER_OK;
 }
 
@@ -241,12 +247,13 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
                              int B, int Hkv, int Dg, int nb_max, int block_size, seer_select_mode mode,
                              int32_t budget_tokens, const int32_t* budget_blocks, double threshold,
                              int32_t* block_idx, int32_t* nblk, int max_sel, void* workspace,
-                             size_t workspace_bytes, void* stream) {
+                             size_t workspace_bytes, uint32_t hints, void* stream) {
   if (!q_gate || !kc_cache || !seqlens || !block_idx || !nblk) return SEER_ERR_NULL;
   if (B <= 0 || Hkv <= 0 || Dg <= 0 || nb_max <= 0 || block_size <= 0 || max_sel <= 0) return SEER_ERR_SHAPE;
   if (B > 65535 || Hkv > 65535) return SEER_ERR_UNSUPPORTED;
   if (Dg != seer::kHeadDim || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
   if (mode != SEER_SELECT_TOPK && mode != SEER_SELECT_THRESHOLD && mode != SEER_SELECT_TOPP) return SEER_ERR_UNSUPPORTED;
+  if (hints & ~(uint32_t)SEER_HINT_RAGGED_LISTS) return SEER_ERR_UNSUPPORTED;
   if ((kc_stride_batch % 8) || (kc_stride_head % 8) || (kc_stride_block % 8) || kc_stride_block < Dg)
     return SEER_ERR_SHAPE;
   if (!aligned16(q_gate) || !aligned16(kc_cache)) return SEER_ERR_SHAPE;
@@ -289,8 +296,9 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
   // computes its scores straight into LDS, then selects) saves a launch and wins only when the
   // whole compression cache is tiny and the step is launch-latency bound.
   bool fused = seer::gate_fused_possible(p) && (size_t)B * Hkv * nb_max * Dg * 2 <= ((size_t)1 << 20);
-  if (g_knob_gate == 1) fused = false;
-  if (g_knob_gate == 2) fused = seer::gate_fused_possible(p);
+  const int gate_impl = g_knob_gate.load(std::memory_order_relaxed);
+  if (gate_impl == 1) fused = false;
+  if (gate_impl == 2) fused = seer::gate_fused_possible(p);
   if (fused) {
     Timed t(SEER_KERNEL_GATE_SELECT, s);
     e = seer::launch_gate_fused(p, s);
@@ -298,7 +306,7 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
   }
   {
     Timed t(SEER_KERNEL_GATE_SCORE, s);
-    e = seer::launch_gate_score(p, g_knob_ragged != 0, s);
+    e = seer::launch_gate_score(p, (hints & SEER_HINT_RAGGED_LISTS) != 0, s);
   }
   if (e != hipSuccess) return SEER_ERR_HIP;
   {
@@ -312,26 +320,26 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv, const in
                                const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int Hq,
                                int Hkv, int d, int block_size, float scale, void* out,
                                seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
-                               void* stream) {
+                               uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, 1, Hq, Hkv, d, block_size, scale,
-                       out, out_dtype, lse, workspace, workspace_bytes, stream);
+                       out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
 }
 
 seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
                                      const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int q_len,
                                      int Hq, int Hkv, int d, int block_size, float scale, void* out,
                                      seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
-                                     void* stream) {
+                                     uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, q_len, Hq, Hkv, d, block_size, scale,
-                       out, out_dtype, lse, workspace, workspace_bytes, stream);
+                       out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
 }
 
 seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int32_t* seqlens, int max_blocks,
                               int B, int Hq, int Hkv, int d, int block_size, float scale, void* out,
                               seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, 1, Hq, Hkv, d, block_size,
-                       scale, out, out_dtype, lse, workspace, workspace_bytes, stream);
+                       scale, out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
 }
 
 seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,
@@ -509,10 +517,6 @@ seer_status seer_set_knob(int knob, int value) {
       if (value < 0) return SEER_ERR_SHAPE;
       g_knob_splits = value;
       return SEER_OK;
-    case SEER_KNOB_DECODE_RAGGED:
-      if (value < 0 || value > 1) return SEER_ERR_SHAPE;
-      g_knob_ragged = value;
-      return SEER_OK;
     case SEER_KNOB_GATE_IMPL:
       if (value < 0 || value > 2) return SEER_ERR_SHAPE;
       g_knob_gate = value;
@@ -526,7 +530,6 @@ seer_status seer_get_knob(int knob, int* value) {
   switch (knob) {
     case SEER_KNOB_DECODE_IMPL: *value = g_knob_impl; return SEER_OK;
     case SEER_KNOB_DECODE_SPLITS: *value = g_knob_splits; return SEER_OK;
-    case SEER_KNOB_DECODE_RAGGED: *value = g_knob_ragged; return SEER_OK;
     case SEER_KNOB_GATE_IMPL: *value = g_knob_gate; return SEER_OK;
     default: return SEER_ERR_UNSUPPORTED;
   }
@@ -544,22 +547,22 @@ seer_status seer_profile_reset(void) {
   return SEER_OK;
 }
 
-seer_status seer_profile_read(int which, int* launches, double* total_ms) {
-  if (!launches || !total_ms) return SEER_ERR_NULL;
-  if (which < 0 || which >= SEER_KERNEL_CLASSES) return SEER_ERR_SHAPE;
+seer_status seer_profile_durations(int which, double* ms, int capacity, int* launches) {
+  if (!launches || (capacity > 0 && !ms)) return SEER_ERR_NULL;
+  if (which < 0 || which >= SEER_KERNEL_CLASSES || capacity < 0) return SEER_ERR_SHAPE;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   int n = 0;
-  double tot = 0.0;
   for (auto& e : g_prof) {
     if (e.cls != which) continue;
-    if (hipEventSynchronize(e.b) != hipSuccess) return SEER_ERR_HIP;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) return SEER_ERR_HIP;
-    tot += ms;
+    if (n < capacity) {
+      if (hipEventSynchronize(e.b) != hipSuccess) return SEER_ERR_HIP;
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, e.a, e.b) != hipSuccess) return SEER_ERR_HIP;
+      ms[n] = t;
+    }
     ++n;
   }
   *launches = n;
-  *total_ms = tot;
   return SEER_OK;
 }
 

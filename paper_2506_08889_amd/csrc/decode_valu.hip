@@ -8,8 +8,8 @@
 // q.k is reduced over the 16 lanes of a row with xor-shuffles.  fp32 accumulation; logits
 // are kept in the base-2 domain (scale*log2(e) folded in) so the exponentials are exp2.
 //
-// This is the reference formulation the MFMA kernel is measured against and the fallback for
-// block sizes that are not a multiple of 32.
+// This is the formulation the MFMA kernel is measured against (selected with SEER_KNOB_DECODE_IMPL);
+// every supported block size runs on either kernel, one new token per call only.
 #include "seer_internal.h"
 
 namespace seer {

@@ -17,6 +17,35 @@ namespace seer {
 // ---------------------------------------------------------------------------------------
 constexpr int kScoreRowsPerWg = 64;
 
+// The query of a group as 8 fp64 values per lane (lane c of 16 holds features 8c .. 8c+7).
+__device__ __forceinline__ void load_gate_query(const uint16_t* q_row, int c, double (&qd)[8]) {
+  const uint4 qr = *reinterpret_cast<const uint4*>(q_row + c * 8);
+  const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    qd[2 * e] = (double)bf16_lo(w[e]);
+    qd[2 * e + 1] = (double)bf16_hi(w[e]);
+  }
+}
+
+// Score of one cache row: each of the 16 lanes that share the row holds 8 of its features in `kr`;
+// exact bf16 products accumulated by fp64 FMAs, then summed over the 16 lanes.  Every lane of the 16
+// returns the score (-0 folded into +0 so that equal scores have equal bit patterns).
+__device__ __forceinline__ double gate_row_score(const uint4& kr, const double (&qd)[8]) {
+  const uint32_t w[4] = {kr.x, kr.y, kr.z, kr.w};
+  double acc = 0.0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
+    acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
+  }
+  acc += __shfl_xor(acc, 1);
+  acc += __shfl_xor(acc, 2);
+  acc += __shfl_xor(acc, 4);
+  acc += __shfl_xor(acc, 8);
+  return acc + 0.0;
+}
+
 __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
   const int i = blockIdx.z, h = blockIdx.y;
   int S = p.seqlens[i];
@@ -30,16 +59,8 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
   const int slot = lane >> 4, c = lane & 15;
   const int64_t grp = (int64_t)i * p.Hkv + h;
 
-  const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
   double qd[8];
-  {
-    const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      qd[2 * e] = (double)bf16_lo(w[e]);
-      qd[2 * e + 1] = (double)bf16_hi(w[e]);
-    }
-  }
+  load_gate_query(p.q_gate + grp * kHeadDim, c, qd);
 
   const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head;
   uint4 kr[4];
@@ -53,19 +74,8 @@ __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
   }
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const uint32_t w[4] = {kr[it].x, kr[it].y, kr[it].z, kr[it].w};
-    double acc = 0.0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
-      acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
-    }
-    // sum over the 16 lanes that share a row
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    acc += __shfl_xor(acc, 8);
-    if (c == 0 && jj[it] < nfull) p.scores[grp * p.nb_max + jj[it]] = acc + 0.0;  // -0 -> +0
+    const double sc = gate_row_score(kr[it], qd);
+    if (c == 0 && jj[it] < nfull) p.scores[grp * p.nb_max + jj[it]] = sc;
   }
 }
 
@@ -87,16 +97,8 @@ __global__ __launch_bounds__(256) void seer_gate_score_walk_kernel(GateParams p)
   const int slot = lane >> 4, c = lane & 15;
   const int64_t grp = (int64_t)i * p.Hkv + h;
 
-  const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
   double qd[8];
-  {
-    const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      qd[2 * e] = (double)bf16_lo(w[e]);
-      qd[2 * e + 1] = (double)bf16_hi(w[e]);
-    }
-  }
+  load_gate_query(p.q_gate + grp * kHeadDim, c, qd);
 
   const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head;
   const int step = gridDim.x * kScoreRowsPerWg;       // the work-groups of a group interleave their tiles
@@ -116,20 +118,9 @@ __global__ __launch_bounds__(256) void seer_gate_score_walk_kernel(GateParams p)
     if (more) load_tile(j0 + step, kn);               // the next tile is in flight during the reduction
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const uint32_t w[4] = {kr[it].x, kr[it].y, kr[it].z, kr[it].w};
-      double acc = 0.0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
-        acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
-      }
-      // sum over the 16 lanes that share a row
-      acc += __shfl_xor(acc, 1);
-      acc += __shfl_xor(acc, 2);
-      acc += __shfl_xor(acc, 4);
-      acc += __shfl_xor(acc, 8);
+      const double sc = gate_row_score(kr[it], qd);
       const int j = j0 + r + it * 4;
-      if (c == 0 && j < nfull) p.scores[grp * p.nb_max + j] = acc + 0.0;  // -0 -> +0
+      if (c == 0 && j < nfull) p.scores[grp * p.nb_max + j] = sc;
     }
     if (more) {
 #pragma unroll
@@ -259,16 +250,8 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     // (32 KiB per work-group) per step, the next step's loads issued before the current reduction.
     double* sl = reinterpret_cast<double*>(dyn_smem);
     const int slot = lane >> 4, c = lane & 15;
-    const uint4 qr = *reinterpret_cast<const uint4*>(p.q_gate + grp * kHeadDim + c * 8);
     double qd[8];
-    {
-      const uint32_t w[4] = {qr.x, qr.y, qr.z, qr.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        qd[2 * e] = (double)bf16_lo(w[e]);
-        qd[2 * e + 1] = (double)bf16_hi(w[e]);
-      }
-    }
+    load_gate_query(p.q_gate + grp * kHeadDim, c, qd);
     const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + c * 8;
     uint4 kr[8], kn[8];
     auto load_rows = [&](int j0, uint4 (&dst)[8]) {
@@ -286,18 +269,8 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int j = j0 + u * 16 + wave * 4 + slot;
-        const uint32_t w[4] = {kr[u].x, kr[u].y, kr[u].z, kr[u].w};
-        double acc = 0.0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
-          acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
-        }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
-        acc += __shfl_xor(acc, 8);
-        if (c == 0 && j < nfull) sl[j] = acc + 0.0;   // -0 -> +0
+        const double sc = gate_row_score(kr[u], qd);
+        if (c == 0 && j < nfull) sl[j] = sc;
       }
       if (more) {
 #pragma unroll
@@ -474,7 +447,10 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
                                 : (p.threshold > 0.0 ? (unsigned long long)(p.threshold * kFix) : 0ull);
       if (want == 0) want = 1;                       // at least the best block
       uint64_t prefix = 0, kmask = 0;
-      bool done = false;
+      // p >= 1 asks for the whole mass; every softmax probability is positive, so only the set of all
+      // full blocks has it (decided here, not left to how the rounded masses happen to add up)
+      bool done = p.threshold >= 1.0;
+      if (done) { T = 0; take_ge = true; }
       for (int pass = 7; pass >= 0 && !done; --pass) {
         const int shift = pass * 8;
         hist[tid] = 0;
@@ -608,20 +584,49 @@ hipError_t launch_gate_score(const GateParams& p, bool ragged, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Dynamic LDS of the select kernel for `nb` blocks held in LDS: fp64 scores + one flag byte each.
+static size_t select_dyn_lds(int nb) { return (size_t)nb * (sizeof(double) + 1); }
+
+// Can a work-group of `kernel` get `dyn` bytes of dynamic LDS on top of its static arrays on the
+// current device?  Requests beyond the 64 KiB every device grants need the function's limit raised
+// first; a device that cannot hold the sum is answered with false (the caller takes another path).
+template <typename K>
+static bool reserve_dyn_lds(K kernel, size_t dyn) {
+  hipFuncAttributes fa;
+  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (fa.sharedSizeBytes + dyn <= 64 * 1024) return true;
+  int dev = 0, max_lds = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  if (fa.sharedSizeBytes + dyn > (size_t)max_lds) return false;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
 hipError_t launch_gate_select(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
-  if (p.nb_max <= kSelectLdsBlocks)
-    hipLaunchKernelGGL(seer_gate_select_kernel<1>, grid, dim3(256), (size_t)p.nb_max * (sizeof(double) + 1), s, p);
-  else
+  const size_t dyn = select_dyn_lds(p.nb_max);
+  if (p.nb_max <= kSelectLdsBlocks && reserve_dyn_lds(seer_gate_select_kernel<1>, dyn))
+    hipLaunchKernelGGL(seer_gate_select_kernel<1>, grid, dim3(256), dyn, s, p);
+  else      // scores stay in global memory (L2): a cache longer than the LDS the device grants
     hipLaunchKernelGGL(seer_gate_select_kernel<0>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
-bool gate_fused_possible(const GateParams& p) { return p.nb_max <= kSelectLdsBlocks; }
+bool gate_fused_possible(const GateParams& p) {
+  return p.nb_max <= kSelectLdsBlocks && reserve_dyn_lds(seer_gate_select_kernel<2>, select_dyn_lds(p.nb_max));
+}
 
 hipError_t launch_gate_fused(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
-  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), (size_t)p.nb_max * (sizeof(double) + 1), s, p);
+  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), select_dyn_lds(p.nb_max), s, p);
   return hipGetLastError();
 }
 

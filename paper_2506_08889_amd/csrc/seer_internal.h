@@ -37,10 +37,10 @@ struct GateParams {
   int64_t kc_stride_batch, kc_stride_head, kc_stride_block;
   const int32_t* seqlens;
   int32_t B, Hkv, nb_max, block_size;
-  int32_t mode;                 // 0 top-k, 1 threshold
+  int32_t mode;                 // seer_select_mode: 0 top-k, 1 threshold, 2 top-p
   int32_t budget_tokens;
   const int32_t* budget_blocks; // [B] or nullptr
-  double threshold;
+  double threshold;             // tau (mode 1) or p (mode 2)
   double inv_sqrt_dg;
   int32_t* block_idx;           // [B,Hkv,max_sel]
   int32_t* nblk;                // [B,Hkv]

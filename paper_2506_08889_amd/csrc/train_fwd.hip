@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       qb[a][kk] = make_uint4(0, 0, 0, 0);
-      if (qrow[a] < p.T)
+      if (qrow[a] < S)                         // padding rows (>= S) compute on zeros: whatever they hold stays out
         qb[a][kk] = *reinterpret_cast<const uint4*>(p.q + (((int64_t)i * p.T + qrow[a]) * p.Hq + h) * kHeadDim +
                                                     kk * 32 + q4 * 8);
     }
@@ -124,8 +124,9 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   // operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).  Whole tiles are
   // fetched straight into LDS (global_load_lds: a wave fills 1 KiB = its 4 rows, lane l at +16*l, so
   // the swizzle is applied to the global address); no staging registers, no LDS store instructions.
-  // The last tile of a sequence whose length is not a multiple of 64 goes through registers with its
-  // missing rows zeroed.
+  // The last tile of a sequence whose length is not a multiple of 64 goes through registers with the
+  // rows at and beyond the sequence's length zeroed: those keys are masked (P = 0), but 0 x NaN or
+  // 0 x Inf from whatever the padding holds would still poison the PV product of the real rows.
   const int srow = tid >> 4, schunk = tid & 15;
   const int wave_rows = __builtin_amdgcn_readfirstlane(wave) * 4;
   const uint16_t* kptr = kbase + (int64_t)srow * st + ((schunk ^ (srow & 15)) * 8);
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   auto fetch_tile = [&](int kt0, unsigned char* kdst, unsigned char* vdst) {
     const uint16_t* kp = kptr + (int64_t)kt0 * st;
     const uint16_t* vp = vptr + (int64_t)kt0 * st;
-    if (kt0 + kKTile <= p.T) {               // work-group-uniform: every row of the tile exists
+    if (kt0 + kKTile <= S) {                 // work-group-uniform: every row of the tile is a real key
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         __builtin_amdgcn_global_load_lds(kp + (int64_t)(16 * u) * st, SEER_LDS_PTR(kdst + (16 * u + wave_rows) * 256),
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
-        if (kt0 + 16 * u + srow < p.T) {
+        if (kt0 + 16 * u + srow < S) {
           kr = *reinterpret_cast<const uint4*>(kp + (int64_t)(16 * u) * st);
           vr = *reinterpret_cast<const uint4*>(vp + (int64_t)(16 * u) * st);
         }

@@ -185,17 +185,22 @@ def make_inputs(w: Workload, device="cpu", seed: Optional[int] = None) -> Decode
     if w.budget_tokens > 0:
         max_sel = min((w.budget_tokens + b - 1) // b, nb_max)
     else:
-        nb_i = (seqlens_cpu.to(torch.int64) + b - 1) // b
-        num = int(round(w.budget_frac * 1000))
-        kb = torch.clamp((nb_i * num + 999) // 1000, min=1)
-        budget_blocks_cpu = kb.to(torch.int32)
+        budget_blocks_cpu = block_budgets(seqlens_cpu, b, w.budget_frac)
         budget_blocks = budget_blocks_cpu.to(dev)
-        max_sel = int(kb.max().item())
+        max_sel = int(budget_blocks_cpu.max().item())
 
     return DecodeInputs(w=w, seqlens=seqlens_cpu.to(dev), seqlens_cpu=seqlens_cpu, q=q, k=k, v=v,
                         page_table=page_table, page_size=page_size, q_gate=q_gate, kc=kc,
                         nb_max=nb_max, budget_blocks=budget_blocks,
                         budget_blocks_cpu=budget_blocks_cpu, max_sel=max_sel)
+
+
+def block_budgets(seqlens_cpu: torch.Tensor, block_size: int, frac: float) -> torch.Tensor:
+    """[B] int32 per-sequence block budgets: the fraction ``frac`` (in thousandths) of each sequence's
+    blocks, rounded up, at least one.  Integer arithmetic only."""
+    nb_i = (seqlens_cpu.to(torch.int64) + block_size - 1) // block_size
+    num = int(round(frac * 1000))
+    return torch.clamp((nb_i * num + 999) // 1000, min=1).to(torch.int32)
 
 
 def random_block_lists(B: int, Hkv: int, nb_per_seq, k_per_seq, max_sel: int, gen_cpu: torch.Generator,

@@ -80,9 +80,9 @@ int main(void) {
   CHECK_HIP(hipStreamCreate(&stream));
 
   CHECK_SEER(seer_gate_select(dqg, dkc, (int64_t)Hkv * NB * D, (int64_t)NB * D, D, dsl, B, Hkv, D, NB, BS, SEER_SELECT_TOPK,
-                              BUDGET, NULL, 0.0, didx, dcnt, MAXSEL, ws_g, wsg, stream));
+                              BUDGET, NULL, 0.0, didx, dcnt, MAXSEL, ws_g, wsg, SEER_HINT_NONE, stream));
   seer_kv_layout kv = {dk, dv, (int64_t)Hkv * SMAX * D, (int64_t)SMAX * D, D, NULL, 0, 0};
-  CHECK_SEER(seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, stream));
+  CHECK_SEER(seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, SEER_HINT_NONE, stream));
   CHECK_HIP(hipStreamSynchronize(stream));
 
   int32_t idx[B * Hkv * MAXSEL], cnt[B * Hkv];
@@ -137,7 +137,7 @@ int main(void) {
   }
 
   /* error paths need no device work */
-  if (seer_sparse_decode(NULL, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, stream) != SEER_ERR_NULL) return 7;
-  if (seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, 16, stream) != SEER_ERR_WORKSPACE) return 7;
+  if (seer_sparse_decode(NULL, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, wsd, SEER_HINT_NONE, stream) != SEER_ERR_NULL) return 7;
+  if (seer_sparse_decode(dq, &kv, dsl, didx, dcnt, MAXSEL, B, Hq, Hkv, D, BS, scale, dout, SEER_F32, dlse, ws_d, 16, SEER_HINT_NONE, stream) != SEER_ERR_WORKSPACE) return 7;
   return 0;
 }

@@ -104,10 +104,12 @@ def pick_threshold(scores, seqlens, block_size, dg, target_keep):
     return float(0.5 * (p[c - 1] + p[c]))
 
 
-def oracle_decode_on_groups(inp, block_idx, nblk, groups):
+def oracle_decode_on_groups(inp, block_idx, nblk, groups, host_kv=None):
     """Oracle decode of a sample of (sequence, kv-head) groups of a large device-resident workload:
     only the sampled groups' K/V (or, for a paged cache, the sampled heads' pools) are copied to
-    the host.  Returns (out [n,g,d], lse [n,g]) in the order of `groups` (flat ids i*Hkv + h)."""
+    the host.  `host_kv` (a dict the caller keeps) caches the host copies of the page pools per kv
+    head across calls on the same tensors.  Returns (out [n,g,d], lse [n,g]) in the order of
+    `groups` (flat ids i*Hkv + h)."""
     w = inp.w
     g, d = w.g, w.d
     groups = np.asarray(groups)
@@ -131,7 +133,13 @@ def oracle_decode_on_groups(inp, block_idx, nblk, groups):
     for h in sorted(set(int(x) for x in hi)):
         m = np.nonzero(hi == h)[0]
         tm = torch.as_tensor(m)
-        kv = KVLayout(inp.k[:, h:h + 1].cpu(), inp.v[:, h:h + 1].cpu(), pt_all[tb[tm]].contiguous(), inp.page_size)
+        if host_kv is not None and h in host_kv:
+            kh, vh = host_kv[h]
+        else:
+            kh, vh = inp.k[:, h:h + 1].cpu(), inp.v[:, h:h + 1].cpu()
+            if host_kv is not None:
+                host_kv[h] = (kh, vh)
+        kv = KVLayout(kh, vh, pt_all[tb[tm]].contiguous(), inp.page_size)
         o, l = oracle.sparse_decode(q_s[tm], kv, sl_s[tm], idx_s[tm], cnt_s[tm], w.block_size, w.scale)
         out[m], lse[m] = o, l
     return out, lse

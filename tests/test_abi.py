@@ -67,8 +67,9 @@ def test_argument_errors_are_reported_before_any_launch():
     f = ctypes.c_float(0.1)
 
     def sparse(q=P, layp=ctypes.byref(lay), sl=P, bi=P, nk=P, max_sel=16, B=1, Hq=8, Hkv=2, d=128, bs=64,
-               out=P, dt=0, lse=P, ws=P, wsb=1 << 30):
-        return lib.seer_sparse_decode(q, layp, sl, bi, nk, max_sel, B, Hq, Hkv, d, bs, f, out, dt, lse, ws, wsb, None)
+               out=P, dt=0, lse=P, ws=P, wsb=1 << 30, hints=0):
+        return lib.seer_sparse_decode(q, layp, sl, bi, nk, max_sel, B, Hq, Hkv, d, bs, f, out, dt, lse, ws, wsb, hints,
+                                      None)
 
     assert sparse(q=None) == -1
     assert sparse(bi=None) == -1
@@ -80,6 +81,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert sparse(bs=48) == -3
     assert sparse(Hq=18) == -3
     assert sparse(dt=5) == -3
+    assert sparse(hints=2) == -3                                 # unknown hint bit
     assert sparse(ws=None) == -4
     assert sparse(wsb=16) == -4
     assert sparse(ws=ctypes.c_void_p(0x10008)) == -4            # misaligned workspace
@@ -91,18 +93,19 @@ def test_argument_errors_are_reported_before_any_launch():
     assert sparse() == -2
     lay.page_table, lay.max_pages, lay.page_size = None, 0, 0
 
-    assert lib.seer_dense_decode(P, ctypes.byref(lay), P, 0, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, None) == -2
-    assert lib.seer_dense_decode(None, ctypes.byref(lay), P, 4, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, None) == -1
+    assert lib.seer_dense_decode(P, ctypes.byref(lay), P, 0, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, 0, None) == -2
+    assert lib.seer_dense_decode(None, ctypes.byref(lay), P, 4, 1, 8, 2, 128, 64, f, P, 0, P, P, 1 << 30, 0, None) == -1
 
     def gate(qg=P, kc=P, sl=P, B=1, Hkv=2, Dg=128, nb_max=64, bs=64, mode=0, budget=1024, bb=None, thr=0.0,
-             bi=P, nk=P, max_sel=16, ws=P, wsb=1 << 30, sj=128):
+             bi=P, nk=P, max_sel=16, ws=P, wsb=1 << 30, sj=128, hints=0):
         return lib.seer_gate_select(qg, kc, 2 * 64 * 128, 64 * 128, sj, sl, B, Hkv, Dg, nb_max, bs, mode, budget,
-                                    bb, thr, bi, nk, max_sel, ws, wsb, None)
+                                    bb, thr, bi, nk, max_sel, ws, wsb, hints, None)
 
     assert gate(qg=None) == -1
     assert gate(nk=None) == -1
     assert gate(Dg=64) == -3
     assert gate(mode=3) == -3
+    assert gate(hints=4) == -3
     assert gate(mode=2, max_sel=16) == -5              # top-p may select every block too
     assert gate(bs=100) == -3
     assert gate(budget=-5) == -2
@@ -115,7 +118,7 @@ def test_argument_errors_are_reported_before_any_launch():
 
 
 def test_knobs_roundtrip():
-    for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0)), (2, (1, 0)), (3, (1, 2, 0))):
+    for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0)), (3, (1, 2, 0))):
         for v in vals:
             seer.set_knob(knob, v)
             assert seer.get_knob(knob) == v
@@ -123,6 +126,8 @@ def test_knobs_roundtrip():
         seer.set_knob(0, 9)
     with pytest.raises(seer.SeerError):
         seer.set_knob(42, 1)
+    with pytest.raises(seer.SeerError):
+        seer.set_knob(2, 1)          # what a caller knows about its lists travels with the call (hints), not a knob
 
 
 def test_split_plan_properties_on_the_host():
@@ -130,22 +135,20 @@ def test_split_plan_properties_on_the_host():
     a slice holds at least 4 entries (or the whole list), there are at most 256 slices, and the plan
     never needs more workspace than the size query hands out."""
     import itertools
-    for knob in (0, 1, 2, 3):
+    for knob in (0, 1, 3):
         seer.set_knob(knob, 0)
     try:
         for ragged, forced in itertools.product((0, 1), (0, 1, 3, 64, 1000)):
-            seer.set_knob(2, ragged)
             seer.set_knob(1, forced)
             for B, Hkv, nb, bs in itertools.product((1, 4, 16, 32, 64, 300), (1, 2, 8), (1, 3, 13, 64, 205, 2048, 5000),
                                                     (16, 64, 128)):
-                ns, per = seer.decode_plan(B, Hkv, nb, bs)
+                ns, per = seer.decode_plan(B, Hkv, nb, bs, ragged=bool(ragged))
                 assert 1 <= ns <= 256 and per >= 1
                 assert ns * per >= nb and (ns - 1) * per < nb          # covers the list, no empty last slice
                 assert per >= min(4, nb) or ns == 1
                 if forced and not ragged:
                     assert ns <= forced
         seer.set_knob(1, 0)
-        seer.set_knob(2, 0)
         # equal-length lists: no cut when there are at least as many groups as compute units, and short
         # lists stay whole when cutting saves less than a merge launch
         assert seer.decode_plan(64, 8, 205, 64) == (1, 205)
@@ -154,7 +157,7 @@ def test_split_plan_properties_on_the_host():
         assert seer.decode_plan(16, 8, 64, 64)[0] == 2
         assert seer.decode_plan(1, 8, 256, 64)[0] == 32
     finally:
-        for knob in (0, 1, 2, 3):
+        for knob in (0, 1, 3):
             seer.set_knob(knob, 0)
     with pytest.raises(seer.SeerError):
         seer.decode_plan(0, 8, 16, 64)

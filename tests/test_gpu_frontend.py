@@ -77,6 +77,39 @@ def test_kc_update_matches_oracle(bs, paged):
         assert (kc2[i, :, :j] == 7.0).all() and (kc2[i, :, j + 1:] == 7.0).all()
 
 
+def test_kc_update_with_two_blocks_per_page():
+    """A paged pre-RoPE key pool whose pages hold two blocks each (page_size = 2 x block_size), shuffled
+    page table, sequences ending inside the first and inside the second block of their last page."""
+    bs, page, B, Hkv = 64, 128, 3, 2
+    sl = torch.tensor([bs * 9 + 17, bs * 6, bs * 4 + 63], dtype=torch.int32)
+    npg = 5                                                   # pages per sequence: 10 blocks
+    gen = synth.generator(DEV, 321)
+    pool = synth.randn_bf16((B * npg + 1, Hkv, page, 128), DEV, gen)
+    order = torch.randperm(B * npg, generator=torch.Generator().manual_seed(5)) + 1
+    pt = order.view(B, npg).to(torch.int32)
+    w = synth.Workload("fk2", B=B, Hq=8, Hkv=Hkv, block_size=bs, seqlen=bs * 10)
+    _, wk = synth.gate_weights(w, DEV, gen)
+    nb_max = 10
+    cos, sin = synth.rope_tables(nb_max * bs + 1, 128, device=DEV)
+    kc = torch.full((B, Hkv, nb_max, 128), 7.0, dtype=torch.bfloat16, device=DEV)
+    seer.kc_update(pool, wk, cos, sin, sl.to(DEV), bs, kc, page_table=pt.to(DEV), page_size=page)
+    torch.cuda.synchronize()
+    ref, bits = oracle.kc_update(pool.cpu(), wk.cpu(), cos.cpu(), sin.cpu(), sl, bs, nb_max, page_table=pt, page_size=page)
+    bf16_close(kc, ref, bits, "kc_update two blocks per page")
+    assert (kc.float().cpu().numpy()[np.isnan(ref)] == 7.0).all()
+    assert (~np.isnan(ref)).reshape(B, Hkv, nb_max, 128)[:, 0, :, 0].sum(1).tolist() == [9, 6, 4]
+    # the newest full block only (second half of a page for the first two sequences, first half for the third)
+    kc2 = torch.full_like(kc, 7.0)
+    nfull = sl // bs
+    seer.kc_update(pool, wk, cos, sin, sl.to(DEV), bs, kc2, max_blocks=1, block_begin=(nfull - 1).to(torch.int32).to(DEV),
+                   block_end=nfull.to(torch.int32).to(DEV), page_table=pt.to(DEV), page_size=page)
+    torch.cuda.synchronize()
+    for i in range(B):
+        j = int(nfull[i]) - 1
+        assert torch.equal(kc2[i, :, j], kc[i, :, j])
+        assert (kc2[i, :, :j] == 7.0).all() and (kc2[i, :, j + 1:] == 7.0).all()
+
+
 def test_front_end_to_decode_chain():
     """Raw pre-RoPE Q/K -> gate inputs -> block selection -> sparse decode, every stage against the
     oracle on the inputs the GPU stage actually received."""

@@ -1,7 +1,9 @@
 """GPU parity at the FULL sizes of the benchmark configurations, in the launch configuration
-bench.py times (default knobs, bf16 output, caller-provided workspaces): every block index of
-every group against the oracle (bit-exact), and the decode output on a sample of (sequence,
-kv-head) groups that always includes the first and the last group."""
+bench.py times (default knobs, the same per-call hints, caller-provided workspaces): every block
+index of every group against the oracle (bit-exact), and the decode output on a sample of (sequence,
+kv-head) groups that always includes the first and the last group - once with bf16 output at the
+contract's bars and once with fp32 output at the tight bars of tests/helpers.py, which a dropped block
+or tail token cannot pass."""
 import numpy as np
 import pytest
 import torch
@@ -22,37 +24,49 @@ def sample_groups(G, n, seed):
     return np.sort(np.concatenate([[0, G - 1], inner]).astype(np.int64))
 
 
-def run_full(name, n_sample, mode=seer.SELECT_TOPK, keep=None, block_size=None):
+def is_ragged(w, mode):
+    """The hint bench.py passes: lists of very different lengths."""
+    return w.seqlen_dist != "fixed" or w.budget_tokens == 0 or mode != seer.SELECT_TOPK
+
+
+def gate_and_decode_full(inp, n_sample, mode=seer.SELECT_TOPK, keep=None, scores=None, host_kv=None, what=""):
+    """Gate on every group (bit-exact), decode on the whole batch, oracle decode on a sample."""
+    w = inp.w
     for k in (0, 1, 3):
         seer.set_knob(k, 0)
-    w = synth.CONFIGS[name]
-    seer.set_knob(2, 1 if (w.seqlen_dist != "fixed" or w.budget_tokens == 0) else 0)   # as bench.py does
-    if block_size:
-        w = synth.scaled(w, block_size=block_size)
-    print(f"[full] {w.name} b={w.block_size} mode={mode}", flush=True)
-    inp = synth.make_inputs(w, DEV)
+    ragged = is_ragged(w, mode)
     max_sel, thr = inp.max_sel, 0.0
     if mode == seer.SELECT_THRESHOLD:
-        _, _, scores = oracle_gate(inp, return_scores=True)
         thr = pick_threshold(scores, inp.seqlens_cpu, w.block_size, w.Dg, keep)
         max_sel = inp.nb_max
+    print(f"[full] {what}: gate, {w.B * w.Hkv} groups, mode={mode} keep={keep} max_sel={max_sel}", flush=True)
     ref_idx, ref_cnt = oracle_gate(inp, mode=mode, threshold=thr, max_sel=max_sel)
     idx, cnt = seer.gate_select(inp.q_gate, inp.kc, inp.seqlens, w.block_size, mode=mode,
                                 budget_tokens=w.budget_tokens, budget_blocks=inp.budget_blocks, threshold=thr,
-                                max_sel=max_sel)
+                                max_sel=max_sel, ragged=ragged)
     torch.cuda.synchronize()
-    check_indices(idx, cnt, ref_idx, ref_cnt, what=f"{w.name} gate (all {w.B * w.Hkv} groups)")
-    out, lse = seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, idx, cnt, w.block_size, w.scale,
-                                  page_table=inp.page_table, page_size=inp.page_size)
-    torch.cuda.synchronize()
+    check_indices(idx, cnt, ref_idx, ref_cnt, what=f"{what} gate (all {w.B * w.Hkv} groups)")
     groups = sample_groups(w.B * w.Hkv, n_sample, w.seed)
-    print(f"[full] {w.name}: oracle decode on {len(groups)} groups", flush=True)
-    ro, rl = oracle_decode_on_groups(inp, ref_idx, ref_cnt, groups)
-    go = gather_groups(out, w, groups, w.g)
-    gl = gather_groups(lse, w, groups, w.g)
-    check_decode(go, gl, ro, rl, tight=False, what=f"{w.name} decode sample")
-    # whole output: finite, and rows of non-empty groups are not all zero
-    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    print(f"[full] {what}: oracle decode on {len(groups)} groups, {int(ref_cnt.sum())} blocks selected in all", flush=True)
+    ro, rl = oracle_decode_on_groups(inp, ref_idx, ref_cnt, groups, host_kv=host_kv)
+    for dt, tight in ((torch.bfloat16, False), (torch.float32, True)):
+        out, lse = seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, idx, cnt, w.block_size, w.scale,
+                                      page_table=inp.page_table, page_size=inp.page_size, out_dtype=dt, ragged=ragged)
+        torch.cuda.synchronize()
+        check_decode(gather_groups(out, w, groups, w.g), gather_groups(lse, w, groups, w.g), ro, rl, tight=tight,
+                     what=f"{what} decode sample {dt}")
+        # whole output finite; lse is -inf exactly for the groups that selected nothing
+        assert torch.isfinite(out.float()).all()
+        empty = (cnt == 0).repeat_interleave(w.g, dim=1)
+        assert torch.equal(torch.isneginf(lse), empty) and torch.isfinite(lse[~empty]).all()
+    return idx, cnt
+
+
+def run_full(name, n_sample, **kw):
+    w = synth.CONFIGS[name]
+    print(f"[full] {w.name} b={w.block_size}: inputs", flush=True)
+    inp = synth.make_inputs(w, DEV)
+    idx, cnt = gate_and_decode_full(inp, n_sample, what=w.name, **kw)
     return inp, idx, cnt
 
 
@@ -64,30 +78,44 @@ def test_c3_full_size_paged():
     run_full("c3", 48)
 
 
+@pytest.mark.timeout(600)
 def test_c4_full_size_headline():
-    inp, idx, cnt = run_full("c4", 24)
-    # the dense flash-decode of the same shape, on a few groups
+    """The headline configuration: 64 sampled groups of 512 (first and last included), bf16 output at
+    the contract's bars and fp32 output at the tight ones; then the dense flash-decode of the same shape."""
+    inp, idx, cnt = run_full("c4", 64)
     w = inp.w
-    out, lse = seer.dense_decode(inp.q, inp.k, inp.v, inp.seqlens, inp.nb_max, w.block_size, w.scale)
-    torch.cuda.synchronize()
     groups = np.array([0, 257, w.B * w.Hkv - 1])
-    ro, rl = oracle_decode_on_groups(inp, None, None, groups) if False else (None, None)
-    # dense oracle: every block listed
     nb = inp.nb_max
     all_idx = torch.arange(nb, dtype=torch.int32).expand(w.B, w.Hkv, nb).contiguous()
     all_cnt = torch.full((w.B, w.Hkv), nb, dtype=torch.int32)
+    print("[full] c4: dense oracle on 3 groups", flush=True)
     ro, rl = oracle_decode_on_groups(inp, all_idx, all_cnt, groups)
-    check_decode(gather_groups(out, w, groups, w.g), gather_groups(lse, w, groups, w.g), ro, rl, tight=False,
-                 what="c4 dense sample")
+    for dt, tight in ((torch.bfloat16, False), (torch.float32, True)):
+        out, lse = seer.dense_decode(inp.q, inp.k, inp.v, inp.seqlens, inp.nb_max, w.block_size, w.scale, out_dtype=dt)
+        torch.cuda.synchronize()
+        check_decode(gather_groups(out, w, groups, w.g), gather_groups(lse, w, groups, w.g), ro, rl, tight=tight,
+                     what=f"c4 dense sample {dt}")
 
 
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("bs", [64, 128])
-def test_c5_full_size_topk(bs):
-    run_full("c5", 32, block_size=bs)
-
-
-def test_c5_full_size_threshold_90pct():
-    run_full("c5", 32, mode=seer.SELECT_THRESHOLD, keep=0.10)
+def test_c5_full_size_sweep_topk_and_threshold(bs):
+    """Batch 128, log-uniform lengths, paged: token-budget and threshold selection at 50 / 75 / 90 / 95 %
+    sparsity.  One set of tensors per block size (the draws do not depend on the budget); indices of all
+    1024 groups, decode on 32 sampled groups per point."""
+    w = synth.scaled(synth.CONFIGS["c5"], block_size=bs)
+    print(f"[full] c5 b={bs}: inputs", flush=True)
+    inp = synth.make_inputs(w, DEV)
+    host_kv = {}                                   # host copies of the sampled heads' page pools, made once
+    _, _, scores = oracle_gate(inp, return_scores=True)
+    for keep in (0.5, 0.25, 0.10, 0.05):
+        inp.w = synth.scaled(w, budget_frac=keep)
+        inp.budget_blocks_cpu = synth.block_budgets(inp.seqlens_cpu, bs, keep)
+        inp.budget_blocks = inp.budget_blocks_cpu.to(DEV)
+        inp.max_sel = int(inp.budget_blocks_cpu.max())
+        gate_and_decode_full(inp, 32, host_kv=host_kv, what=f"c5 b={bs} top-k keep={keep}")
+        gate_and_decode_full(inp, 32, mode=seer.SELECT_THRESHOLD, keep=keep, scores=scores, host_kv=host_kv,
+                             what=f"c5 b={bs} threshold keep={keep}")
 
 
 def test_training_forward_long_sequence_every_row():

@@ -96,6 +96,29 @@ def test_sequence_lengths_and_padding_rows(seer):
     check(seer, q, k, v, 64, 0.09, seqlens=sl)
 
 
+def test_padding_may_hold_anything(seer):
+    """Rows at and beyond a sequence's length are padding: NaN / Inf there (queries, keys and values)
+    must not reach any real row - a masked key has probability 0, but 0 x NaN would still be NaN in the
+    PV product - and the padding rows themselves come out as exact zeros."""
+    q, k, v = make(6, 3, 300, 4, 2)
+    sl_cpu = [257, 130, 64]                      # mid-tile, two keys into a tile, exactly one tile
+    for i, s in enumerate(sl_cpu):
+        q[i, s:] = float("nan")
+        k[i, :, s:] = float("inf")
+        v[i, :, s:] = float("nan")
+    sl = torch.tensor(sl_cpu, dtype=torch.int32, device=DEV)
+    out, lse, gt = seer.attn_ground_truth(q, k, v, 64, 0.09, seqlens=sl, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and torch.isfinite(gt).all()
+    qz, kz, vz = q.clone(), k.clone(), v.clone()       # the oracle on the same real rows, padding zeroed
+    for i, s in enumerate(sl_cpu):
+        qz[i, s:] = 0; kz[i, :, s:] = 0; vz[i, :, s:] = 0
+    check(seer, qz, kz, vz, 64, 0.09, seqlens=sl)
+    o2, l2, g2 = seer.attn_ground_truth(qz, kz, vz, 64, 0.09, seqlens=sl, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(out, o2) and torch.equal(lse, l2) and torch.equal(gt, g2)
+
+
 def test_strided_kv_and_longer_cache(seer):
     # K/V are views into a longer, interleaved cache: [B, S_alloc, Hkv, D] storage read as [B,Hkv,S,D]
     gen = synth.generator(DEV, 5)
