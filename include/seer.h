@@ -48,7 +48,8 @@ typedef enum seer_status {
   SEER_ERR_UNSUPPORTED = -3, /* valid but not implemented (d, Dg, block size, g)    */
   SEER_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small          */
   SEER_ERR_CAPACITY = -5,    /* max_sel cannot hold the selection that was asked for */
-  SEER_ERR_HIP = -6          /* a HIP runtime call failed (launch error)            */
+  SEER_ERR_HIP = -6,         /* a HIP runtime call failed (launch error)            */
+  SEER_ERR_SCRATCH = -7      /* seer_sparse_decode_noalloc: the call needs more than the built-in scratch */
 } seer_status;
 
 typedef enum seer_select_mode {
@@ -174,6 +175,30 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv /* host s
                                int block_size, float scale, void* out, seer_dtype out_dtype,
                                float* lse, void* workspace, size_t workspace_bytes, uint32_t hints,
                                void* stream);
+
+/*
+ * seer_sparse_decode for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation,
+ * same kernels and same results as seer_sparse_decode; the split-K partials go to a scratch array of
+ * SEER_NOALLOC_SCRATCH_BYTES that is part of the library image (each GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates and frees nothing.
+ *   - Limit: the plan of the call (seer_decode_plan) must fit the array:
+ *       2 * align256(B * Hkv * num_splits * (Hq/Hkv) * 4 * {128, 2} bytes)  <=  SEER_NOALLOC_SCRATCH_BYTES,
+ *     about B * Hkv * num_splits * (Hq/Hkv) <= 64 000 partial rows; with a single slice (num_splits
+ *     == 1) nothing is stored there at all.  Larger calls return SEER_ERR_SCRATCH before anything is
+ *     launched.
+ *   - All calls on one GPU share that GPU's array.  Nothing in it has to be cleared between calls
+ *     (every partial a merge reads was written by the split kernel of the same call), but two calls
+ *     that overlap on one GPU (different streams or threads) race on it: keep them on one stream.
+ *   - The first call on each device looks up the array's device address (once per device, host work
+ *     only); make that first call outside stream capture.
+ */
+#define SEER_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+seer_status seer_sparse_decode_noalloc(const void* q, const seer_kv_layout* kv /* host struct */,
+                                       const int32_t* seqlens, const int32_t* block_idx,
+                                       const int32_t* nblk, int max_sel, int B, int Hq, int Hkv, int d,
+                                       int block_size, float scale, void* out, seer_dtype out_dtype,
+                                       float* lse, uint32_t hints, void* stream);
 
 /*
  * Several new tokens per sequence in one call - the multi-token / speculative decoding direction of

@@ -18,6 +18,7 @@ SELECT_TOPK = 0
 SELECT_THRESHOLD = 1
 SELECT_TOPP = 2
 HINT_RAGGED_LISTS = 1
+NOALLOC_SCRATCH_BYTES = 32 << 20
 KNOB_DECODE_IMPL = 0
 KNOB_DECODE_SPLITS = 1
 KNOB_GATE_IMPL = 3
@@ -76,6 +77,10 @@ def load_library():
     lib.seer_sparse_decode.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int,
                                        c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
                                        c_vp, c_sz, c_u32, c_vp]
+    lib.seer_sparse_decode_noalloc.restype = c_int
+    lib.seer_sparse_decode_noalloc.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int,
+                                               c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
+                                               c_u32, c_vp]
     lib.seer_sparse_decode_multi.restype = c_int
     lib.seer_sparse_decode_multi.argtypes = [c_vp, ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_int, c_int,
                                              c_int, c_int, c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp,
@@ -255,6 +260,35 @@ def sparse_decode(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: to
                                 0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _ptr(workspace),
                                 workspace.numel(), _hints(ragged), _stream())
     _check("seer_sparse_decode", st)
+    return out, lse
+
+
+def sparse_decode_noalloc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, seqlens: torch.Tensor,
+                          block_idx: torch.Tensor, nblk: torch.Tensor, block_size: int, scale: float, *,
+                          out: torch.Tensor, lse: torch.Tensor, page_table: Optional[torch.Tensor] = None,
+                          page_size: int = 0, ragged: bool = False):
+    """seer_sparse_decode_noalloc: seer_sparse_decode on the library's built-in scratch array.  Neither
+    the library nor this wrapper allocates: out [B,Hq,d] (bf16 or fp32) and lse [B,Hq] fp32 are the
+    caller's.  Returns (out, lse)."""
+    lib = load_library()
+    _want(q, torch.bfloat16, "q"); _want(seqlens, torch.int32, "seqlens")
+    _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk"); _want(lse, torch.float32, "lse")
+    if not (q.is_contiguous() and block_idx.is_contiguous() and nblk.is_contiguous() and out.is_contiguous()
+            and lse.is_contiguous()):
+        raise ValueError("q, block_idx, nblk, out and lse must be contiguous")
+    if out.dtype not in (torch.bfloat16, torch.float32) or not out.is_cuda:
+        raise TypeError("out must be a bf16 or fp32 device tensor")
+    B, Hq, d = q.shape
+    if tuple(out.shape) != (B, Hq, d) or tuple(lse.shape) != (B, Hq):
+        raise ValueError("out must be [B,Hq,d] and lse [B,Hq]")
+    Hkv = k.shape[1]
+    max_sel = block_idx.shape[2]
+    lay = _layout(k, v, page_table, page_size)
+    st = lib.seer_sparse_decode_noalloc(_ptr(q), ctypes.byref(lay), _ptr(seqlens), _ptr(block_idx), _ptr(nblk),
+                                        max_sel, B, Hq, Hkv, d, block_size, ctypes.c_float(scale), _ptr(out),
+                                        0 if out.dtype == torch.bfloat16 else 1, _ptr(lse), _hints(ragged),
+                                        _stream())
+    _check("seer_sparse_decode_noalloc", st)
     return out, lse
 
 

@@ -11,6 +11,9 @@
 
 #include "seer_internal.h"
 
+// Scratch memory of seer_sparse_decode_noalloc: part of the library's code object, one copy per GPU.
+static __device__ __align__(256) unsigned char scratch[SEER_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 // Measurement / test knobs (seer_set_knob).  Atomic so that a setter on one thread never tears a
@@ -123,11 +126,40 @@ struct Timed {
 bool block_size_ok(int bs) { return bs == 16 || bs == 32 || bs == 64 || bs == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---- built-in scratch of the entry point that allocates nothing --------------------------------
+// Device memory that lives in the library's code object: every GPU that loads the library holds its
+// own copy at its own address until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; the address it returns (per device) is what kernels receive.
+constexpr size_t kNoAllocScratchBytes = SEER_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Address of `scratch` on the current device; looked up once per device, with that device current.
+seer_status scratch_of_current_device(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SEER_ERR_HIP; }
+  if (dev < 0 || dev >= kMaxDevices) return SEER_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return SEER_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return SEER_OK;
+}
+
+// builtin_scratch: the split-K partials go to the library's own `scratch` array instead of a caller
+// workspace (workspace / workspace_bytes are ignored).
 seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
                           const int32_t* block_idx, const int32_t* nblk, int max_blocks, bool sparse,
                           int B, int q_len, int Hq, int Hkv, int d, int block_size, float scale, void* out,
                           seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
-                          uint32_t hints, void* stream) {
+                          bool builtin_scratch, uint32_t hints, void* stream) {
   if (!q || !kv || !seqlens || !out) return SEER_ERR_NULL;
   if (!kv->k || !kv->v) return SEER_ERR_NULL;
   if (sparse && (!block_idx || !nblk)) return SEER_ERR_NULL;
@@ -151,9 +183,16 @@ seer_status decode_common(const void* q, const seer_kv_layout* kv, const int32_t
   }
   int ns, len;
   plan_splits(B, Hkv, max_blocks, block_size, (hints & SEER_HINT_RAGGED_LISTS) != 0, &ns, &len);
-  const size_t need = decode_ws_bytes(B, Hkv, rows, max_splits_for(max_blocks));
-  if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-    return SEER_ERR_WORKSPACE;
+  if (builtin_scratch) {
+    // the plan of this very call must fit the array; checked on the host, before the device is touched
+    if (decode_ws_bytes(B, Hkv, rows, ns) > kNoAllocScratchBytes) return SEER_ERR_SCRATCH;
+    const seer_status st = scratch_of_current_device(&workspace);
+    if (st != SEER_OK) return st;
+  } else {
+    const size_t need = decode_ws_bytes(B, Hkv, rows, max_splits_for(max_blocks));
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+      return SEER_ERR_WORKSPACE;
+  }
 
   seer::DecodeParams p{};
   p.q = static_cast<const uint16_t*>(q);
@@ -213,6 +252,7 @@ const char* seer_status_string(int status) {
     case SEER_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SEER_ERR_CAPACITY: return "max_sel cannot hold the requested selection";
     case SEER_ERR_HIP: return "HIP runtime error";
+    case SEER_ERR_SCRATCH: return "the call needs more than the built-in scratch buffer of the no-allocation entry point";
     default: return "unknown status";
   }
 }
@@ -322,7 +362,15 @@ seer_status seer_sparse_decode(const void* q, const seer_kv_layout* kv, const in
                                seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                                uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, 1, Hq, Hkv, d, block_size, scale,
-                       out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
+                       out, out_dtype, lse, workspace, workspace_bytes, false, hints, stream);
+}
+
+seer_status seer_sparse_decode_noalloc(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
+                                       const int32_t* block_idx, const int32_t* nblk, int max_sel, int B, int Hq,
+                                       int Hkv, int d, int block_size, float scale, void* out,
+                                       seer_dtype out_dtype, float* lse, uint32_t hints, void* stream) {
+  return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, 1, Hq, Hkv, d, block_size, scale,
+                       out, out_dtype, lse, nullptr, 0, true, hints, stream);
 }
 
 seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv, const int32_t* seqlens,
@@ -331,7 +379,7 @@ seer_status seer_sparse_decode_multi(const void* q, const seer_kv_layout* kv, co
                                      seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                                      uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, block_idx, nblk, max_sel, true, B, q_len, Hq, Hkv, d, block_size, scale,
-                       out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
+                       out, out_dtype, lse, workspace, workspace_bytes, false, hints, stream);
 }
 
 seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int32_t* seqlens, int max_blocks,
@@ -339,7 +387,7 @@ seer_status seer_dense_decode(const void* q, const seer_kv_layout* kv, const int
                               seer_dtype out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                               uint32_t hints, void* stream) {
   return decode_common(q, kv, seqlens, nullptr, nullptr, max_blocks, false, B, 1, Hq, Hkv, d, block_size,
-                       scale, out, out_dtype, lse, workspace, workspace_bytes, hints, stream);
+                       scale, out, out_dtype, lse, workspace, workspace_bytes, false, hints, stream);
 }
 
 seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,

@@ -31,11 +31,11 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     lib = seer.load_library()
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = lib.seer_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert lib.seer_status_string(-99).decode() == "unknown status"
 
 
