@@ -70,6 +70,8 @@ __global__ __launch_bounds__(128) void seer_decode_merge_kernel(DecodeParams p) 
   }
   for (; s < nsv; ++s) a += pa[(int64_t)s * g * kHeadDim + tid] * wgt[s];
   store_output(p, output_row(p, i, hk, h), tid, tot[0], tot[1], a);
+  // every unit of the split kernel has been handed out: leave its hand-out word valid and at zero
+  if (p.sched && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.sched = (unsigned long long)kSchedMagic << 32;
 }
 
 hipError_t launch_decode_merge(const DecodeParams& p, hipStream_t s) {

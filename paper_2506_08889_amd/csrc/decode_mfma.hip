@@ -67,15 +67,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 }  // namespace
 
+// 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
+constexpr int kSliceLdsBytes = 4 * 32 * 256 + 4 * kMaxRows * 2 * 4;
+
+// One slice of one group's list, by one work-group of 4 waves: slice `split` of (sequence i, kv head hk).
 // ROWS128: stride_token == 128 elements (rows back to back), so every row offset is an immediate.
 // B16: 16-token blocks, two list entries per 32-row step.
 template <bool ROWS128, bool B16>
-__global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodeParams p) {
-  // 4 waves x (32 rows x 256 B) K staging; reused for the final cross-wave merge.
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * 256 + 4 * kMaxRows * 2 * 4];
-
-  int split, hk, i;
-  decode_wg_coords(p, &split, &hk, &i);
+__device__ __forceinline__ void decode_slice(const DecodeParams& p, unsigned char* smem, const int i, const int hk,
+                                             const int split) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
   const int g = p.g, rows = p.rows;
@@ -438,9 +438,161 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
   }
 }
 
+// Grid (Hkv, B, num_splits): one work-group per (group, slice).
+template <bool ROWS128, bool B16>
+__global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodeParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kSliceLdsBytes];
+  int split, hk, i;
+  decode_wg_coords(p, &split, &hk, &i);
+  decode_slice<ROWS128, B16>(p, smem, i, hk, split);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Lists of very different lengths: a fixed set of W work-groups (two per compute unit) walks the slices
+// that exist instead of one work-group per (group, slice of the list capacity), most of which would
+// find nothing to do and only hold a slot while they find out (a threshold selection may list every
+// block, so the capacity is the whole sequence).
+//   Round 0: work-group w takes the first slice of group w straight away, like the grid kernel would.
+//   Then every work-group derives the same table of the remaining units from the groups' counts:
+//     [0, G - W)   first slices of the groups W .. G-1 (when there are more groups than work-groups),
+//     then         the further slices of full length of all groups, in group order,
+//     then         the shorter last slices - so the launch ends on short units.
+//   Units are handed out through a counter in the workspace - whichever work-group is free takes the
+//   next one, so compute units that get less of the memory system take fewer - or, when the counter
+//   does not hold a valid state (first use of a workspace), round-robin.  The partial result of a unit
+//   does not depend on who computes it, so results stay bit-identical from run to run.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kMaxPersistGroups = 2048;
+
+template <bool ROWS128, bool B16>
+__global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(DecodeParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kSliceLdsBytes];
+  __shared__ int pfx_full[kMaxPersistGroups + 1];   // exclusive prefix of the groups' full-length slices after the first
+  __shared__ int pfx_rem[kMaxPersistGroups + 1];    // ... and of their shorter last slices after the first (0 or 1 each)
+  __shared__ int wsum[2][4];
+  __shared__ int s_next, s_dynamic;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int G = p.B * p.Hkv, L = p.blocks_per_split, W = gridDim.x, w = blockIdx.x;
+
+  if (w < G) decode_slice<ROWS128, B16>(p, smem, w / p.Hkv, w % p.Hkv, 0);
+  if (p.num_splits == 1) {                    // the list capacity fits one slice: nothing but first slices
+    for (int grp = w + W; grp < G; grp += W) {
+      __syncthreads();
+      decode_slice<ROWS128, B16>(p, smem, grp / p.Hkv, grp % p.Hkv, 0);
+    }
+    return;
+  }
+
+  // ---- hand-out word [kSchedMagic - taken : 32 | taken : 32]: one add moves one from the high half to
+  // the low half, so high + low == kSchedMagic holds for every state that started valid and all
+  // work-groups reach the same verdict.  The merge kernel of the call leaves it reset.
+  constexpr unsigned long long kTake = 0xFFFFFFFF00000001ull;
+  unsigned long long took = 0;
+  if (tid == 0 && p.sched) took = __hip_atomic_fetch_add(p.sched, kTake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- unit table: thread t owns groups [t*per, (t+1)*per) ---------------------------------------
+  {
+    const int per = (G + 255) / 256;
+    const int g0 = tid * per;
+    int f_sum = 0, r_sum = 0;
+    for (int u = 0; u < per; ++u) {
+      const int grp = g0 + u;
+      if (grp >= G) break;
+      int n;
+      if (p.block_idx) {
+        n = p.nblk[grp];
+        n = n < 0 ? 0 : (n < p.max_blocks ? n : p.max_blocks);
+      } else {
+        int S = p.seqlens[grp / p.Hkv];
+        S = S < 0 ? 0 : S;
+        const int nb = (S + p.block_size - 1) / p.block_size;
+        n = nb < p.max_blocks ? nb : p.max_blocks;
+      }
+      const int full = n / L;
+      pfx_full[grp] = f_sum;                  // local exclusive prefix, made global below
+      pfx_rem[grp] = r_sum;
+      f_sum += full > 0 ? full - 1 : 0;
+      r_sum += (full > 0 && n % L != 0) ? 1 : 0;
+    }
+    int fi = f_sum, ri = r_sum;               // inclusive scan over the threads
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int xf = __shfl_up(fi, o), xr = __shfl_up(ri, o);
+      if (lane >= o) { fi += xf; ri += xr; }
+    }
+    __syncthreads();                          // round 0 is done with its LDS; wsum is free
+    if (lane == 63) { wsum[0][wave] = fi; wsum[1][wave] = ri; }
+    __syncthreads();
+    int fo = fi - f_sum, ro = ri - r_sum;
+    for (int ww = 0; ww < wave; ++ww) { fo += wsum[0][ww]; ro += wsum[1][ww]; }
+    for (int u = 0; u < per; ++u) {
+      const int grp = g0 + u;
+      if (grp >= G) break;
+      pfx_full[grp] += fo;
+      pfx_rem[grp] += ro;
+    }
+    if (tid == 255) {
+      pfx_full[G] = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+      pfx_rem[G] = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+    }
+    if (tid == 0) {
+      const bool valid = p.sched && (uint32_t)(took >> 32) + (uint32_t)took == kSchedMagic;
+      s_next = valid ? (int)(uint32_t)took : w;
+      s_dynamic = valid ? 1 : 0;
+    }
+    __syncthreads();
+  }
+  const int first_more = G > W ? G - W : 0;   // first slices that round 0 did not cover
+  const int UF = pfx_full[G], D = first_more + UF + pfx_rem[G];
+  const bool dynamic = s_dynamic != 0;
+  int d = s_next;
+  __syncthreads();
+
+  while (d < D) {
+    int grp, split;
+    if (d < first_more) {
+      grp = W + d;
+      split = 0;
+    } else {
+      const int k = d - first_more;
+      const bool is_full = k < UF;
+      const int* pfx = is_full ? pfx_full : pfx_rem;
+      const int key = is_full ? k : k - UF;
+      int lo = 0, hi = G;                     // invariant: pfx[lo] <= key < pfx[hi]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (pfx[mid] <= key) lo = mid; else hi = mid;
+      }
+      // pfx[lo] <= key < pfx[lo + 1]: group lo owns the unit (groups without a unit of this kind repeat
+      // their successor's prefix value and are never landed on)
+      grp = lo;
+      split = is_full ? 1 + key - pfx_full[grp] : 1 + pfx_full[grp + 1] - pfx_full[grp];
+    }
+    decode_slice<ROWS128, B16>(p, smem, grp / p.Hkv, grp % p.Hkv, split);
+    if (tid == 0)
+      s_next = dynamic ? (int)(uint32_t)__hip_atomic_fetch_add(p.sched, kTake, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                       : d + W;
+    __syncthreads();                          // next unit known; the slice's LDS (K tiles / merge arrays) is free again
+    d = s_next;
+    __syncthreads();
+  }
+}
+
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s) {
-  const dim3 grid = decode_grid(p);
   const bool rows128 = p.stride_token == kHeadDim;
+  if (p.persist_wgs > 0) {
+    const dim3 grid(p.persist_wgs);
+    if (p.block_size == 16) {
+      if (rows128) hipLaunchKernelGGL((seer_decode_persist_mfma_kernel<true, true>), grid, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((seer_decode_persist_mfma_kernel<false, true>), grid, dim3(256), 0, s, p);
+    } else {
+      if (rows128) hipLaunchKernelGGL((seer_decode_persist_mfma_kernel<true, false>), grid, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((seer_decode_persist_mfma_kernel<false, false>), grid, dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+  }
+  const dim3 grid = decode_grid(p);
   if (p.block_size == 16) {
     if (rows128) hipLaunchKernelGGL((seer_decode_split_mfma_kernel<true, true>), grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL((seer_decode_split_mfma_kernel<false, true>), grid, dim3(256), 0, s, p);
@@ -450,5 +602,7 @@ hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s) {
   }
   return hipGetLastError();
 }
+
+bool decode_persist_possible(int groups) { return groups <= kMaxPersistGroups; }
 
 }  // namespace seer

@@ -8,6 +8,8 @@ namespace seer {
 constexpr int kHeadDim = 128;   // d and d_gate; one row is 256 bytes = 16 lanes x 16 B
 constexpr int kMaxGroup = 8;    // query heads per kv head
 constexpr int kMaxRows = 16;    // query rows (new tokens x heads of a group) per kv head = one MFMA tile side
+constexpr uint32_t kSchedMagic = 0x5EE7C0DEu;   // high half + low half of a valid unit hand-out word
+constexpr size_t kDecodeWsHeader = 256;         // bytes in front of the partials: the hand-out word
 
 struct DecodeParams {
   const uint16_t* q;            // bf16 [B,q_len,Hq,128]
@@ -24,6 +26,8 @@ struct DecodeParams {
   int32_t q_len, rows;          // new tokens per sequence (1 = plain decode), rows = q_len * g
   float scale_log2e;            // scale * log2(e): logits are kept in the base-2 domain
   int32_t num_splits, blocks_per_split;
+  int32_t persist_wgs;          // > 0: that many work-groups walk the slices that exist (ragged lists), else one per (group, slice)
+  unsigned long long* sched;    // workspace word handing out units to them, or nullptr (round-robin)
   float* part_acc;              // [B*Hkv, num_splits, rows, 128] unnormalised partial outputs
   float* part_ml;               // [B*Hkv, num_splits, rows, 2]   running max (base-2 domain), sum
   void* out;                    // [B,q_len,Hq,128] bf16 or fp32
@@ -106,6 +110,7 @@ hipError_t launch_gate_fused(const GateParams& p, hipStream_t s);
 hipError_t launch_decode_split_valu(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_split_mfma(const DecodeParams& p, hipStream_t s);
 hipError_t launch_decode_merge(const DecodeParams& p, hipStream_t s);
+bool decode_persist_possible(int groups);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int wgs, hipStream_t s);
 
 // ---- device helpers -------------------------------------------------------------------

@@ -668,6 +668,43 @@ def test_multi_token_decode_on_a_paged_cache():
         seer.set_knob(1, 0)
 
 
+@pytest.mark.parametrize("B,Hkv,smax", [(7, 2, 64 * 400), (80, 8, 64 * 90), (300, 8, 64 * 40)])
+def test_ragged_lists_hint_hand_out_of_slices(B, Hkv, smax):
+    """With the ragged-lists hint a fixed set of work-groups walks the slices that exist: fewer groups than
+    work-groups, more groups than work-groups (the first slices of the later groups are handed out too) and
+    more groups than the unit table holds (falls back to one work-group per slice).  A workspace full of
+    arbitrary bytes (hand-out word invalid: round-robin), the same workspace again (word left valid by
+    the merge: handed out by the counter) and a zeroed one must give bit-identical results; threshold-like
+    lists from empty to nearly everything; dense decode on the same mixed lengths."""
+    g, bs = 2, 64
+    w = synth.Workload("ragged", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen_range=(1, smax), seqlen_dist="loguniform",
+                       paged=True, budget_tokens=0, budget_frac=0.5, seed=B)
+    inp = synth.make_inputs(w, DEV)
+    nb = (inp.seqlens_cpu + bs - 1) // bs
+    rng = np.random.default_rng(B)
+    k_sel = [int(rng.integers(0, int(n) + 1)) for n in nb]             # 0 .. all blocks of the sequence
+    idx, cnt = synth.random_block_lists(B, Hkv, nb, k_sel, inp.nb_max, torch.Generator().manual_seed(B), ascending=False)
+    cnt[0, 0] = 0                                                      # an empty list among non-empty ones
+    ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+    d_idx, d_cnt = idx.to(DEV), cnt.to(DEV)
+    nbytes = seer.decode_workspace_bytes(B, w.Hq, Hkv, w.d, inp.nb_max)
+    ws = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV)
+    outs = []
+    for label, wsp in (("arbitrary bytes", ws), ("same workspace again", ws), ("zeros", torch.zeros_like(ws))):
+        out, lse = seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, d_idx, d_cnt, bs, w.scale, page_table=inp.page_table,
+                                      page_size=inp.page_size, out_dtype=torch.float32, workspace=wsp, ragged=True)
+        torch.cuda.synchronize()
+        check_decode(out, lse, ref_out, ref_lse, tight=True, what=f"ragged B={B} ({label})")
+        outs.append((out.clone(), lse.clone()))
+    for o, l in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(l, outs[0][1]), "the hand-out order changed a result"
+    dref_out, dref_lse = oracle_decode(inp, None, None)
+    out, lse = seer.dense_decode(inp.q, inp.k, inp.v, inp.seqlens, inp.nb_max, bs, w.scale, page_table=inp.page_table,
+                                 page_size=inp.page_size, out_dtype=torch.float32, ragged=True)
+    torch.cuda.synchronize()
+    check_decode(out, lse, dref_out, dref_lse, tight=True, what=f"ragged dense B={B}")
+
+
 def test_bursts_and_overlapping_streams():
     """200 back-to-back calls without a synchronisation, then calls overlapping on two streams (each
     with its own query set, outputs and workspace): results identical to the same calls made alone.
