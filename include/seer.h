@@ -246,6 +246,23 @@ seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_co
                         void* q_gate, void* stream);
 
 /*
+ * AttnGate from the raw query (Eq. 1a followed by Eq. 1c and the selection of Sec. 3.1): what
+ * seer_gate_q followed by seer_gate_select computes, as one call of a decode step.  The gate query of
+ * every (sequence, kv head) is made once by a small kernel in front of the score kernel and kept in
+ * the workspace; pass q_gate_out (bf16 [B,Hkv,Dg], device) to receive it, or NULL.  Arguments as in
+ * the two calls; the workspace is the one of seer_gate_select (seer_gate_workspace_bytes covers both).
+ * All host-visible argument errors of both calls are reported before anything is launched.
+ */
+seer_status seer_gate_select_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,
+                               int n_pos, const void* kc_cache, int64_t kc_stride_batch, int64_t kc_stride_head,
+                               int64_t kc_stride_block, const int32_t* seqlens, int B, int Hq, int Hkv, int d, int Dg,
+                               int nb_max, int block_size, seer_select_mode mode, int32_t budget_tokens,
+                               const int32_t* budget_blocks, double threshold,
+                               int32_t* block_idx /* out [B,Hkv,max_sel] */, int32_t* nblk /* out [B,Hkv] */,
+                               int max_sel, void* q_gate_out /* out or NULL */, void* workspace,
+                               size_t workspace_bytes, uint32_t hints, void* stream);
+
+/*
  * AttnGate front-end, K branch = K Compression Cache update (Eq. 1b, Sec. 3.2): for every
  * sequence i, kv head h and block j in [block_begin[i], block_end[i]) (defaults 0 and
  * seqlens[i]/block_size; always clamped to the full blocks of the sequence and to nb_max): the

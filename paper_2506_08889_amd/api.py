@@ -90,6 +90,10 @@ def load_library():
                                       c_int, c_int, ctypes.c_float, c_vp, c_int, c_vp, c_vp, c_sz, c_u32, c_vp]
     lib.seer_gate_q.restype = c_int
     lib.seer_gate_q.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
+    lib.seer_gate_select_q.restype = c_int
+    lib.seer_gate_select_q.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_vp, c_i64, c_i64, c_i64, c_vp, c_int, c_int, c_int,
+                                       c_int, c_int, c_int, c_int, c_int, ctypes.c_int32, c_vp, ctypes.c_double, c_vp,
+                                       c_vp, c_int, c_vp, c_vp, c_sz, c_u32, c_vp]
     lib.seer_kc_update.restype = c_int
     lib.seer_kc_update.argtypes = [ctypes.POINTER(_KVLayout), c_vp, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_int, c_int,
                                    c_int, c_int, c_int, c_int, c_int, c_vp, c_i64, c_i64, c_i64, c_vp]
@@ -420,6 +424,51 @@ def gate_q(q_nope: torch.Tensor, wq: torch.Tensor, rope_cos: torch.Tensor, rope_
                          d, Dg, _ptr(q_gate), _stream())
     _check("seer_gate_q", st)
     return q_gate
+
+
+def gate_select_q(q_nope: torch.Tensor, wq: torch.Tensor, rope_cos: torch.Tensor, rope_sin: torch.Tensor,
+                  kc_cache: torch.Tensor, seqlens: torch.Tensor, block_size: int, *, mode: int = SELECT_TOPK,
+                  budget_tokens: int = 0, budget_blocks: Optional[torch.Tensor] = None, threshold: float = 0.0,
+                  max_sel: int, block_idx: Optional[torch.Tensor] = None, nblk: Optional[torch.Tensor] = None,
+                  q_gate: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, ragged: bool = False):
+    """seer_gate_select_q: gate query from the pre-RoPE queries (q_nope [B,Hq,d], wq [Hkv,Dg,g*d], rope
+    tables) and block selection against kc_cache in one call.  q_gate (bf16 [B,Hkv,Dg]) receives the gate
+    query when given.  Returns (block_idx, nblk)."""
+    lib = load_library()
+    _want(q_nope, torch.bfloat16, "q_nope"); _want(wq, torch.bfloat16, "wq"); _want(kc_cache, torch.bfloat16, "kc_cache")
+    _want(seqlens, torch.int32, "seqlens")
+    if not (q_nope.is_contiguous() and wq.is_contiguous() and seqlens.is_contiguous()):
+        raise ValueError("q_nope, wq and seqlens must be contiguous")
+    B, Hq, d = q_nope.shape
+    Hkv, Dg, gd = wq.shape
+    if Hq % Hkv or gd != (Hq // Hkv) * d:
+        raise ValueError("wq must be [Hkv, Dg, (Hq/Hkv)*d]")
+    if kc_cache.dim() != 4 or kc_cache.shape[0] != B or kc_cache.shape[1] != Hkv or kc_cache.shape[3] != Dg or \
+            kc_cache.stride(3) != 1:
+        raise ValueError("kc_cache must be [B,Hkv,nb_max,Dg], contiguous in its last dim")
+    n_pos = _rope(rope_cos, rope_sin, Dg)
+    nb_max = kc_cache.shape[2]
+    dev = q_nope.device
+    if block_idx is None:
+        block_idx = torch.empty(B, Hkv, max_sel, dtype=torch.int32, device=dev)
+    if nblk is None:
+        nblk = torch.empty(B, Hkv, dtype=torch.int32, device=dev)
+    _want(block_idx, torch.int32, "block_idx"); _want(nblk, torch.int32, "nblk")
+    if budget_blocks is not None:
+        _want(budget_blocks, torch.int32, "budget_blocks")
+    if q_gate is not None:
+        _want(q_gate, torch.bfloat16, "q_gate")
+        if tuple(q_gate.shape) != (B, Hkv, Dg) or not q_gate.is_contiguous():
+            raise ValueError("q_gate must be contiguous [B,Hkv,Dg]")
+    if workspace is None:
+        workspace = _workspace(gate_workspace_bytes(B, Hkv, nb_max), dev)
+    st = lib.seer_gate_select_q(_ptr(q_nope), _ptr(wq), _ptr(rope_cos), _ptr(rope_sin), n_pos, _ptr(kc_cache),
+                                kc_cache.stride(0), kc_cache.stride(1), kc_cache.stride(2), _ptr(seqlens), B, Hq, Hkv, d,
+                                Dg, nb_max, block_size, mode, int(budget_tokens), _ptr(budget_blocks), float(threshold),
+                                _ptr(block_idx), _ptr(nblk), max_sel, _ptr(q_gate), _ptr(workspace), workspace.numel(),
+                                _hints(ragged), _stream())
+    _check("seer_gate_select_q", st)
+    return block_idx, nblk
 
 
 def kc_update(k_nope: torch.Tensor, wk: torch.Tensor, rope_cos: torch.Tensor, rope_sin: torch.Tensor,

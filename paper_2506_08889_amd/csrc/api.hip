@@ -268,10 +268,13 @@ const char* seer_status_string(int status) {
   }
 }
 
+// Gate workspace: fp64 scores of every block, then the gate queries of seer_gate_select_q.
+static size_t gate_scores_bytes(int B, int Hkv, int nb_max) { return align_up((size_t)B * Hkv * nb_max * sizeof(double), 256); }
+
 seer_status seer_gate_workspace_bytes(int B, int Hkv, int nb_max, size_t* bytes) {
   if (!bytes) return SEER_ERR_NULL;
   if (B <= 0 || Hkv <= 0 || nb_max <= 0) return SEER_ERR_SHAPE;
-  *bytes = align_up((size_t)B * Hkv * nb_max * sizeof(double), 256);
+  *bytes = gate_scores_bytes(B, Hkv, nb_max) + align_up((size_t)B * Hkv * seer::kHeadDim * sizeof(uint16_t), 256);
   return SEER_OK;
 }
 
@@ -426,6 +429,46 @@ seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_co
     e = seer::launch_gate_q(p, s);
   }
   return e == hipSuccess ? SEER_OK : SEER_ERR_HIP;
+}
+
+seer_status seer_gate_select_q(const void* q_nope, const void* wq, const float* rope_cos, const float* rope_sin,
+                               int n_pos, const void* kc_cache, int64_t kc_stride_batch, int64_t kc_stride_head,
+                               int64_t kc_stride_block, const int32_t* seqlens, int B, int Hq, int Hkv, int d, int Dg,
+                               int nb_max, int block_size, seer_select_mode mode, int32_t budget_tokens,
+                               const int32_t* budget_blocks, double threshold, int32_t* block_idx, int32_t* nblk,
+                               int max_sel, void* q_gate_out, void* workspace, size_t workspace_bytes, uint32_t hints,
+                               void* stream) {
+  // The gate query of every group is made once, by a small kernel in front of the score kernel (the
+  // 128 x g*128 matrix-vector product is far too much to repeat in each of the score kernel's
+  // work-groups), into the tail of the workspace unless the caller wants to see it.
+  if (!workspace || B <= 0 || Hkv <= 0 || nb_max <= 0) return !workspace ? SEER_ERR_WORKSPACE : SEER_ERR_SHAPE;
+  size_t need = 0;
+  seer_gate_workspace_bytes(B, Hkv, nb_max, &need);
+  if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return SEER_ERR_WORKSPACE;
+  void* q_gate = q_gate_out ? q_gate_out : static_cast<char*>(workspace) + gate_scores_bytes(B, Hkv, nb_max);
+  // validate the selection's arguments before the first launch (NULL kc_cache etc. must not leave a
+  // half-done call behind): the checks of seer_gate_select that do not depend on q_gate
+  if (!kc_cache || !seqlens || !block_idx || !nblk) return SEER_ERR_NULL;
+  if (block_size <= 0 || max_sel <= 0) return SEER_ERR_SHAPE;
+  if (B > 65535 || Hkv > 65535 || !block_size_ok(block_size)) return SEER_ERR_UNSUPPORTED;
+  if (mode != SEER_SELECT_TOPK && mode != SEER_SELECT_THRESHOLD && mode != SEER_SELECT_TOPP) return SEER_ERR_UNSUPPORTED;
+  if (hints & ~(uint32_t)SEER_HINT_RAGGED_LISTS) return SEER_ERR_UNSUPPORTED;
+  if ((kc_stride_batch % 8) || (kc_stride_head % 8) || (kc_stride_block % 8) || kc_stride_block < Dg) return SEER_ERR_SHAPE;
+  if (!aligned16(kc_cache)) return SEER_ERR_SHAPE;
+  if (mode == SEER_SELECT_THRESHOLD || mode == SEER_SELECT_TOPP) {
+    if (!(threshold == threshold)) return SEER_ERR_SHAPE;
+    if (max_sel < nb_max) return SEER_ERR_CAPACITY;
+  } else if (!budget_blocks) {
+    if (budget_tokens < 0) return SEER_ERR_SHAPE;
+    long k = ((long)budget_tokens + block_size - 1) / block_size;
+    if (k > nb_max) k = nb_max;
+    if (max_sel < k) return SEER_ERR_CAPACITY;
+  }
+  seer_status st = seer_gate_q(q_nope, wq, rope_cos, rope_sin, n_pos, seqlens, B, Hq, Hkv, d, Dg, q_gate, stream);
+  if (st != SEER_OK) return st;
+  return seer_gate_select(q_gate, kc_cache, kc_stride_batch, kc_stride_head, kc_stride_block, seqlens, B, Hkv, Dg, nb_max,
+                          block_size, mode, budget_tokens, budget_blocks, threshold, block_idx, nblk, max_sel, workspace,
+                          workspace_bytes, hints, stream);
 }
 
 seer_status seer_kc_update(const seer_kv_layout* k_nope, const void* wk, const float* rope_cos,

@@ -6,8 +6,9 @@
 // Both are a batch of matrix-vector products against one weight matrix per kv head, so 16 vectors
 // are processed together as the N side of v_mfma_f32_16x16x32_bf16 (operand layout as in
 // decode_mfma.hip: lane = 16*q + n; A row n, B column n, k = 8q..8q+7; D column n, rows 4q..4q+3).
-// The 128 output features are 8 M-tiles; wave w owns tiles w and w + 4, i.e. features
-// [16w, 16w+16) and their rotate-half partners [64+16w, 64+16w+16), so RoPE is lane-local.
+// The 128 output features are 8 M-tiles; a wave (K branch) or a work-group (Q branch) owns tiles t and
+// t + 4, i.e. features [16t, 16t+16) and their rotate-half partners [64+16t, 64+16t+16), so RoPE is
+// lane-local.
 #include "seer_internal.h"
 
 namespace seer {
@@ -43,41 +44,82 @@ __device__ __forceinline__ void rope_store(const f32x4_t& lo, const f32x4_t& hi,
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
-// Q branch.  Grid (ceil(B/16), Hkv); a work-group handles 16 sequences of one kv head.
-// B operand straight from q_nope (the g heads of a group are contiguous: g*128 features).
+// Q branch.  Grid (ceil(B/16), Hkv, 4); a work-group computes, for 16 sequences of one kv head, the
+// 16 output features [16z, 16z+16) and their rotate-half partners (+64).  The g*128 input features
+// are cut into 4g steps of 32; wave v takes steps [v*g, (v+1)*g) and issues all of its loads at once
+// (B operand straight from q_nope - the g heads of a group are contiguous - and two weight rows per
+// lane), so the kernel is one memory round trip deep; the four partial tiles are added in wave order
+// through LDS and wave 0 applies RoPE and stores.  (The first form walked the whole input per wave in
+// g dependent rounds: 13.9 us at batch 64 against the launch floor this one sits on.)
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void seer_gate_q_kernel(FrontQParams p) {
-  const int h = blockIdx.y, i0 = blockIdx.x * 16;
+  __shared__ float part[3][2][64][4];                // partial tiles of waves 1..3
+
+  const int h = blockIdx.y, i0 = blockIdx.x * 16, z = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, q4 = lane >> 4;
-  const int gd = p.g * kHeadDim;
+  const int g = p.g, gd = g * kHeadDim;
   const int i = i0 + n16;
   const bool valid = i < p.B;
 
-  const uint16_t* x = p.q_nope + ((int64_t)(valid ? i : 0) * p.Hq + (int64_t)h * p.g) * kHeadDim + q4 * 8;
-  const uint16_t* w0 = p.wq + ((int64_t)h * kHeadDim + 16 * wave + n16) * gd + q4 * 8;
+  int64_t pos = 0;
+  if (wave == 0 && valid) pos = (int64_t)p.seqlens[i] - 1;          // requested first: the rotation angles depend on it
+
+  const uint16_t* x = p.q_nope + ((int64_t)(valid ? i : 0) * p.Hq + (int64_t)h * g) * kHeadDim + wave * g * 32 + q4 * 8;
+  const uint16_t* w0 = p.wq + ((int64_t)h * kHeadDim + 16 * z + n16) * gd + wave * g * 32 + q4 * 8;
   const uint16_t* w1 = w0 + (int64_t)64 * gd;
-  f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-  for (int kk0 = 0; kk0 < gd / 32; kk0 += 4) {     // gd / 32 = 4 g: always a multiple of 4
-    uint4 b[4], a0[4], a1[4];
+  uint4 b[kMaxGroup], a0[kMaxGroup], a1[kMaxGroup];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < kMaxGroup; ++u) {
+    if (u < g) {
       b[u] = make_uint4(0, 0, 0, 0);
-      if (valid) b[u] = *reinterpret_cast<const uint4*>(x + (kk0 + u) * 32);
-      a0[u] = *reinterpret_cast<const uint4*>(w0 + (kk0 + u) * 32);
-      a1[u] = *reinterpret_cast<const uint4*>(w1 + (kk0 + u) * 32);
+      if (valid) b[u] = *reinterpret_cast<const uint4*>(x + u * 32);
+      a0[u] = *reinterpret_cast<const uint4*>(w0 + u * 32);
+      a1[u] = *reinterpret_cast<const uint4*>(w1 + u * 32);
     }
+  }
+  const int c0 = 16 * z + 4 * q4;                     // this lane's features c0..c0+3 (and +64)
+  float4 co = make_float4(1.f, 1.f, 1.f, 1.f), si = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (wave == 0 && valid) {
+    pos = pos < 0 ? 0 : (pos >= p.n_pos ? p.n_pos - 1 : pos);
+    co = *reinterpret_cast<const float4*>(p.rope_cos + pos * (kHeadDim / 2) + c0);
+    si = *reinterpret_cast<const float4*>(p.rope_sin + pos * (kHeadDim / 2) + c0);
+  }
+  f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < kMaxGroup; ++u) {
+    if (u < g) {
       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a0[u]), __builtin_bit_cast(bf16x8_t, b[u]), acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a1[u]), __builtin_bit_cast(bf16x8_t, b[u]), acc1, 0, 0, 0);
     }
   }
-  if (!valid) return;
-  int64_t pos = (int64_t)p.seqlens[i] - 1;
-  pos = pos < 0 ? 0 : (pos >= p.n_pos ? p.n_pos - 1 : pos);
-  rope_store(acc0, acc1, p.rope_cos, p.rope_sin, pos, 16 * wave + 4 * q4,
-             p.q_gate + ((int64_t)i * p.Hkv + h) * kHeadDim);
+  if (wave > 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      part[wave - 1][0][lane][r] = acc0[r];
+      part[wave - 1][1][lane][r] = acc1[r];
+    }
+  }
+  __syncthreads();
+  if (wave != 0 || !valid) return;
+#pragma unroll
+  for (int v = 0; v < 3; ++v)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      acc0[r] += part[v][0][lane][r];
+      acc1[r] += part[v][1][lane][r];
+    }
+  // rotate-half RoPE on the lane's two accumulators (features c and c + 64) and store
+  const float cv[4] = {co.x, co.y, co.z, co.w}, sv[4] = {si.x, si.y, si.z, si.w};
+  float zl[4], zh[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    zl[r] = acc0[r] * cv[r] - acc1[r] * sv[r];
+    zh[r] = acc1[r] * cv[r] + acc0[r] * sv[r];
+  }
+  uint16_t* dst = p.q_gate + ((int64_t)i * p.Hkv + h) * kHeadDim;
+  *reinterpret_cast<uint2*>(dst + c0) = make_uint2(pack2_bf16_rne(zl[0], zl[1]), pack2_bf16_rne(zl[2], zl[3]));
+  *reinterpret_cast<uint2*>(dst + kHeadDim / 2 + c0) = make_uint2(pack2_bf16_rne(zh[0], zh[1]), pack2_bf16_rne(zh[2], zh[3]));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -269,7 +311,7 @@ __global__ __launch_bounds__(256, 2) void seer_kc_update_kernel(FrontKParams p) 
 }
 
 hipError_t launch_gate_q(const FrontQParams& p, hipStream_t s) {
-  dim3 grid((p.B + 15) / 16, p.Hkv);
+  dim3 grid((p.B + 15) / 16, p.Hkv, 4);
   hipLaunchKernelGGL(seer_gate_q_kernel, grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }

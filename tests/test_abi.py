@@ -117,6 +117,25 @@ def test_argument_errors_are_reported_before_any_launch():
     assert gate(wsb=8) == -4
 
 
+def test_gate_select_q_argument_errors_come_before_the_gate_query_kernel():
+    """The one-call gate validates the arguments of both of its halves before launching the first."""
+    lib = seer.load_library()
+    P = ctypes.c_void_p(0x10000)
+
+    def call(qn=P, wq=P, cos=P, sin=P, kc=P, sl=P, B=2, Hq=8, Hkv=2, d=128, Dg=128, nb_max=64, bs=64, mode=0, budget=1024,
+             thr=0.0, bi=P, nk=P, max_sel=16, ws=P, wsb=1 << 30, hints=0):
+        return lib.seer_gate_select_q(qn, wq, cos, sin, 4097, kc, 2 * 64 * 128, 64 * 128, 128, sl, B, Hq, Hkv, d, Dg, nb_max,
+                                      bs, mode, budget, None, thr, bi, nk, max_sel, None, ws, wsb, hints, None)
+
+    assert call(ws=None) == -4 and call(wsb=64) == -4
+    assert call(kc=None) == -1 and call(nk=None) == -1
+    assert call(bs=48) == -3 and call(mode=7) == -3 and call(hints=2) == -3
+    assert call(max_sel=8) == -5 and call(mode=1, max_sel=16) == -5
+    assert call(budget=-1) == -2
+    assert call(qn=None) == -1 and call(wq=None) == -1 and call(cos=None) == -1      # the query half's own checks
+    assert call(Hq=7) == -2 and call(d=64) == -3
+
+
 def test_knobs_roundtrip():
     for knob, vals in ((0, (1, 2, 0)), (1, (3, 17, 0)), (3, (1, 2, 0))):
         for v in vals:

@@ -110,6 +110,45 @@ def test_kc_update_with_two_blocks_per_page():
         assert (kc2[i, :, :j] == 7.0).all() and (kc2[i, :, j + 1:] == 7.0).all()
 
 
+@pytest.mark.parametrize("g,B,nb_max,bs", [(4, 5, 300, 64), (5, 37, 700, 64), (8, 3, 40, 128), (1, 20, 90, 32)])
+def test_gate_select_q_is_gate_q_then_gate_select(g, B, nb_max, bs):
+    """The one-call form (gate query from the raw queries, then selection): its gate query against the
+    oracle's Eq. 1a, its indices bit-exact against the oracle's selection run on that gate query, and both
+    identical to the two separate calls; with and without asking for the gate query; token budget and
+    threshold selection."""
+    Hkv = 2
+    w = synth.Workload("gsq", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen=nb_max * bs)
+    gen = synth.generator(DEV, 700 + g)
+    q_nope = synth.randn_bf16((B, w.Hq, w.d), DEV, gen)
+    wq, _ = synth.gate_weights(w, DEV, gen)
+    kc = synth.randn_bf16((B, Hkv, nb_max, w.Dg), DEV, gen)
+    cos, sin = synth.rope_tables(nb_max * bs + 1, w.Dg, device=DEV)
+    sl = torch.randint(1, nb_max * bs + 1, (B,), generator=torch.Generator().manual_seed(g), dtype=torch.int32)
+    sl[0] = nb_max * bs
+    sld = sl.to(DEV)
+    k_sel = max(1, nb_max // 8)
+    qg = torch.zeros(B, Hkv, w.Dg, dtype=torch.bfloat16, device=DEV)
+    idx, cnt = seer.gate_select_q(q_nope, wq, cos, sin, kc, sld, bs, budget_tokens=k_sel * bs, max_sel=k_sel, q_gate=qg)
+    torch.cuda.synchronize()
+    rq, rq_bits = oracle.gate_q(q_nope.cpu(), wq.cpu(), cos.cpu(), sin.cpu(), sl)
+    bf16_close(qg, rq, rq_bits, f"gate_select_q q_gate g={g}")
+    ri, rc = oracle.gate_select(qg.cpu(), kc.cpu(), sl, bs, budget_tokens=k_sel * bs, max_sel=k_sel)
+    check_indices(idx, cnt, ri, rc, what=f"gate_select_q top-k g={g}")
+    qg2 = seer.gate_q(q_nope, wq, cos, sin, sld)
+    i2, c2 = seer.gate_select(qg2, kc, sld, bs, budget_tokens=k_sel * bs, max_sel=k_sel)
+    i3, c3 = seer.gate_select_q(q_nope, wq, cos, sin, kc, sld, bs, budget_tokens=k_sel * bs, max_sel=k_sel)
+    torch.cuda.synchronize()
+    assert torch.equal(qg2, qg) and torch.equal(i2, idx) and torch.equal(c2, cnt) and torch.equal(i3, idx) and torch.equal(c3, cnt)
+    from helpers import pick_threshold
+    _, _, scores = oracle.gate_select(qg.cpu(), kc.cpu(), sl, bs, budget_tokens=bs, max_sel=1, return_scores=True)
+    tau = pick_threshold(scores, sl, bs, w.Dg, 0.2)
+    ri, rc = oracle.gate_select(qg.cpu(), kc.cpu(), sl, bs, mode=oracle.SELECT_THRESHOLD, threshold=tau, max_sel=nb_max)
+    idx, cnt = seer.gate_select_q(q_nope, wq, cos, sin, kc, sld, bs, mode=seer.SELECT_THRESHOLD, threshold=tau, max_sel=nb_max,
+                                  ragged=True)
+    torch.cuda.synchronize()
+    check_indices(idx, cnt, ri, rc, what=f"gate_select_q threshold g={g}")
+
+
 def test_front_end_to_decode_chain():
     """Raw pre-RoPE Q/K -> gate inputs -> block selection -> sparse decode, every stage against the
     oracle on the inputs the GPU stage actually received."""
