@@ -456,7 +456,8 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 //   Then every work-group derives the same table of the remaining units from the groups' counts:
 //     [0, G - W)   first slices of the groups W .. G-1 (when there are more groups than work-groups),
 //     then         the further slices of full length of all groups, in group order,
-//     then         the shorter last slices - so the launch ends on short units.
+//     then         the shorter last slices, first those at least half as long, then the rest - so the
+//                  launch ends on its shortest units.
 //   Units are handed out through a counter in the workspace - whichever work-group is free takes the
 //   next one, so compute units that get less of the memory system take fewer - or, when the counter
 //   does not hold a valid state (first use of a workspace), round-robin.  The partial result of a unit
@@ -468,8 +469,9 @@ template <bool ROWS128, bool B16>
 __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSliceLdsBytes];
   __shared__ int pfx_full[kMaxPersistGroups + 1];   // exclusive prefix of the groups' full-length slices after the first
-  __shared__ int pfx_rem[kMaxPersistGroups + 1];    // ... and of their shorter last slices after the first (0 or 1 each)
-  __shared__ int wsum[2][4];
+  __shared__ int pfx_rem[kMaxPersistGroups + 1];    // ... of their shorter last slices after the first that hold >= L/2 entries
+  __shared__ int pfx_tail[kMaxPersistGroups + 1];   // ... and of those that hold fewer (0 or 1 each): the launch ends on these
+  __shared__ int wsum[3][4];
   __shared__ int s_next, s_dynamic;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -495,7 +497,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
   {
     const int per = (G + 255) / 256;
     const int g0 = tid * per;
-    int f_sum = 0, r_sum = 0;
+    int f_sum = 0, r_sum = 0, t_sum = 0;
     for (int u = 0; u < per; ++u) {
       const int grp = g0 + u;
       if (grp >= G) break;
@@ -509,32 +511,36 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
         const int nb = (S + p.block_size - 1) / p.block_size;
         n = nb < p.max_blocks ? nb : p.max_blocks;
       }
-      const int full = n / L;
+      const int full = n / L, rest = n % L;
       pfx_full[grp] = f_sum;                  // local exclusive prefix, made global below
       pfx_rem[grp] = r_sum;
+      pfx_tail[grp] = t_sum;
       f_sum += full > 0 ? full - 1 : 0;
-      r_sum += (full > 0 && n % L != 0) ? 1 : 0;
+      r_sum += (full > 0 && rest != 0 && 2 * rest >= L) ? 1 : 0;
+      t_sum += (full > 0 && rest != 0 && 2 * rest < L) ? 1 : 0;
     }
-    int fi = f_sum, ri = r_sum;               // inclusive scan over the threads
+    int fi = f_sum, ri = r_sum, ti = t_sum;   // inclusive scan over the threads
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-      const int xf = __shfl_up(fi, o), xr = __shfl_up(ri, o);
-      if (lane >= o) { fi += xf; ri += xr; }
+      const int xf = __shfl_up(fi, o), xr = __shfl_up(ri, o), xt = __shfl_up(ti, o);
+      if (lane >= o) { fi += xf; ri += xr; ti += xt; }
     }
     __syncthreads();                          // round 0 is done with its LDS; wsum is free
-    if (lane == 63) { wsum[0][wave] = fi; wsum[1][wave] = ri; }
+    if (lane == 63) { wsum[0][wave] = fi; wsum[1][wave] = ri; wsum[2][wave] = ti; }
     __syncthreads();
-    int fo = fi - f_sum, ro = ri - r_sum;
-    for (int ww = 0; ww < wave; ++ww) { fo += wsum[0][ww]; ro += wsum[1][ww]; }
+    int fo = fi - f_sum, ro = ri - r_sum, to = ti - t_sum;
+    for (int ww = 0; ww < wave; ++ww) { fo += wsum[0][ww]; ro += wsum[1][ww]; to += wsum[2][ww]; }
     for (int u = 0; u < per; ++u) {
       const int grp = g0 + u;
       if (grp >= G) break;
       pfx_full[grp] += fo;
       pfx_rem[grp] += ro;
+      pfx_tail[grp] += to;
     }
     if (tid == 255) {
       pfx_full[G] = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
       pfx_rem[G] = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+      pfx_tail[G] = wsum[2][0] + wsum[2][1] + wsum[2][2] + wsum[2][3];
     }
     if (tid == 0) {
       const bool valid = p.sched && (uint32_t)(took >> 32) + (uint32_t)took == kSchedMagic;
@@ -544,7 +550,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
     __syncthreads();
   }
   const int first_more = G > W ? G - W : 0;   // first slices that round 0 did not cover
-  const int UF = pfx_full[G], D = first_more + UF + pfx_rem[G];
+  const int UF = pfx_full[G], UR = pfx_rem[G], D = first_more + UF + UR + pfx_tail[G];
   const bool dynamic = s_dynamic != 0;
   int d = s_next;
   __syncthreads();
@@ -557,8 +563,8 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
     } else {
       const int k = d - first_more;
       const bool is_full = k < UF;
-      const int* pfx = is_full ? pfx_full : pfx_rem;
-      const int key = is_full ? k : k - UF;
+      const int* pfx = is_full ? pfx_full : (k < UF + UR ? pfx_rem : pfx_tail);
+      const int key = is_full ? k : (k < UF + UR ? k - UF : k - UF - UR);
       int lo = 0, hi = G;                     // invariant: pfx[lo] <= key < pfx[hi]
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
