@@ -48,9 +48,10 @@ def kernel_sources_hash() -> str:
     return h.hexdigest()[:16]
 
 
-def committed_traffic(workload: str):
-    """Hardware-counter HBM bytes per launch of the decode split kernel, or None when there is no
-    committed measurement for this workload or it was taken on other kernel sources."""
+def committed_traffic(workload: str, key: str = "decode_bytes"):
+    """Hardware-counter HBM bytes per launch (key "decode_bytes": split kernel plus merge kernel where one
+    runs; "gate_bytes": score plus select kernel), or None when there is no committed measurement for
+    this workload or it was taken on other kernel sources."""
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
             rec = json.load(f)
@@ -58,7 +59,7 @@ def committed_traffic(workload: str):
         return None
     if rec.get("kernel_sources_sha256_16") != kernel_sources_hash():
         return None
-    return rec.get(workload, {}).get("decode_split_bytes")
+    return rec.get(workload, {}).get(key)
 
 
 def stats_us(ms_list):
@@ -243,7 +244,8 @@ class Bench:
                          "frac_at_min_duration": ab["decode"] / ((split["min"] + (merge["min"] if merge else 0.0)) * 1e-6) / 1e9 / HBM_PEAK_GBPS},
             "gate_roofline": {"bound": "hbm", "kernel": "seer_gate_score + seer_gate_select",
                               "achieved": ab["gate"] / (gate_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": ab["gate"] / (gate_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                              "frac": ab["gate"] / (gate_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                              "traffic": committed_traffic(self.w.name, "gate_bytes") if self.mode == self.seer.SELECT_TOPK else None,
                               "algorithmic_bytes_per_launch": ab["gate"], "avg_kernel_us": gate_us},
         }
         if dense_steps > 0:
