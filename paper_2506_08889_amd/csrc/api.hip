@@ -345,11 +345,13 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  // A wide score kernel (every CU streams cache rows) followed by the select kernel is the faster
-  // form at scale (measured: c4 61 us vs 66 us fused).  The fused kernel (one work-group per group
-  // computes its scores straight into LDS, then selects) saves a launch and wins only when the
-  // whole compression cache is tiny and the step is launch-latency bound.
-  bool fused = seer::gate_fused_possible(p) && (size_t)B * Hkv * nb_max * Dg * 2 <= ((size_t)1 << 20);
+  // The fused kernel (one work-group per group computes its scores straight into LDS, then selects)
+  // saves a launch and the score workspace and is the faster form up to mid-size caches (measured,
+  // step of gate + decode: batch 16 x 32k tokens 58.8 vs 59.9 us, batch 32 x 8k-64k tokens at block 128 106.7 vs
+  // 109.4 us).  At scale a wide score kernel (every CU streams cache rows from the first microsecond)
+  // followed by the select kernel wins: a batch of 64 x 128k-token caches has exactly two groups per
+  // CU, all of which finish streaming and then select at the same time (step 580 vs 558 us).
+  bool fused = seer::gate_fused_possible(p) && (size_t)B * Hkv * nb_max * Dg * 2 <= ((size_t)128 << 20);
   const int gate_impl = g_knob_gate.load(std::memory_order_relaxed);
   if (gate_impl == 1) fused = false;
   if (gate_impl == 2) fused = seer::gate_fused_possible(p);

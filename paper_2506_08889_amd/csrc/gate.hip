@@ -17,6 +17,58 @@ namespace seer {
 // ---------------------------------------------------------------------------------------
 constexpr int kScoreRowsPerWg = 64;
 
+// ---------------------------------------------------------------------------------------
+// Cross-lane steps on the VALU's data-parallel lane moves (no trip through the LDS crossbar, so a
+// chain of them costs tens of cycles instead of many hundreds).  Controls: quad_perm [1,0,3,2] = 0xB1,
+// quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140, row_shr:n = 0x110 + n.
+// ---------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ int lane_move_i32(int x) {     // lanes without a source lane receive 0
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double lane_move_f64(double x) {
+  return __hiloint2double(lane_move_i32<CTRL>(__double2hiint(x)), lane_move_i32<CTRL>(__double2loint(x)));
+}
+__device__ __forceinline__ double readlane_f64(double x, int l) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l), __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+// Sum / maximum over each row of 16 lanes, delivered to all 16 (pairs, quads, halves, row: the same tree
+// in every lane, so all 16 hold the same bits).
+__device__ __forceinline__ double row16_sum_f64(double x) {
+  x += lane_move_f64<0xB1>(x);
+  x += lane_move_f64<0x4E>(x);
+  x += lane_move_f64<0x141>(x);
+  x += lane_move_f64<0x140>(x);
+  return x;
+}
+__device__ __forceinline__ double row16_max_f64(double x) {
+  x = fmax(x, lane_move_f64<0xB1>(x));
+  x = fmax(x, lane_move_f64<0x4E>(x));
+  x = fmax(x, lane_move_f64<0x141>(x));
+  x = fmax(x, lane_move_f64<0x140>(x));
+  return x;
+}
+// ... and over the 64 lanes of a wave (uniform result).
+__device__ __forceinline__ double wave_sum_f64(double x) {
+  x = row16_sum_f64(x);
+  return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
+}
+__device__ __forceinline__ double wave_max_f64(double x) {
+  x = row16_max_f64(x);
+  return fmax(fmax(readlane_f64(x, 0), readlane_f64(x, 16)), fmax(readlane_f64(x, 32), readlane_f64(x, 48)));
+}
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ int wave_inclusive_scan_i32(int x) {
+  x += lane_move_i32<0x111>(x);
+  x += lane_move_i32<0x112>(x);
+  x += lane_move_i32<0x114>(x);
+  x += lane_move_i32<0x118>(x);
+  const int r0 = __builtin_amdgcn_readlane(x, 15), r1 = __builtin_amdgcn_readlane(x, 31), r2 = __builtin_amdgcn_readlane(x, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return x + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
+}
+
 // The query of a group as 8 fp64 values per lane (lane c of 16 holds features 8c .. 8c+7).
 __device__ __forceinline__ void load_gate_query(const uint16_t* q_row, int c, double (&qd)[8]) {
   const uint4 qr = *reinterpret_cast<const uint4*>(q_row + c * 8);
@@ -39,11 +91,7 @@ __device__ __forceinline__ double gate_row_score(const uint4& kr, const double (
     acc = fma((double)bf16_lo(w[e]), qd[2 * e], acc);
     acc = fma((double)bf16_hi(w[e]), qd[2 * e + 1], acc);
   }
-  acc += __shfl_xor(acc, 1);
-  acc += __shfl_xor(acc, 2);
-  acc += __shfl_xor(acc, 4);
-  acc += __shfl_xor(acc, 8);
-  return acc + 0.0;
+  return row16_sum_f64(acc) + 0.0;
 }
 
 __global__ __launch_bounds__(256) void seer_gate_score_kernel(GateParams p) {
@@ -145,12 +193,17 @@ __global__ __launch_bounds__(256) void seer_gate_score_walk_kernel(GateParams p)
 //              index first.
 //   threshold: fp64 softmax over the full blocks (max, sum of exp, divide), S_j > tau.
 //   top-p:     the radix walk steered by probability mass (2^-62 fixed point, exact sums).
-//   Either way an ordered compaction emits the ascending list: each thread owns a contiguous
-//   run of block ids, counts its hits, one work-group scan gives its offset.
+//   Either way an ordered compaction emits the ascending list: thread t owns blocks t, t + 256, ...;
+//   per row of 256 blocks a wave ballot ranks the hits inside the wave and the four waves' counts, laid
+//   out in LDS, give the offset of every (row, wave) - one barrier, every score classified once.
+// A work-group has two waves per SIMD at most, so nothing hides instruction latency here: reductions
+// and scans inside a wave run on lane moves in the VALU (see the helpers above), every work-group step
+// costs one barrier, and state is cleared while the scores are still on their way.
 // ---------------------------------------------------------------------------------------
 constexpr int kSelectLdsBlocks = 8192;
 constexpr int kLinBins = 1024;    // top-k fast path: bins over [min score, max score]
 constexpr int kMaxCand = 256;     // ... and the most blocks its boundary bin may hold
+constexpr int kMaxOwn = kSelectLdsBlocks / 256;   // blocks per thread and pass of the ordered compaction
 
 __device__ __forceinline__ uint64_t score_key(double s) {
   const uint64_t b = (uint64_t)__double_as_longlong(s);
@@ -163,63 +216,111 @@ __device__ __forceinline__ int lin_bin_of(double s, double lo, double scale) {
   return b < 0 ? 0 : (b > kLinBins - 1 ? kLinBins - 1 : b);
 }
 
-__device__ __forceinline__ double wg_reduce_max(double x, double* sm) {
+// f(j, score) for the blocks j = t, t + 256, ... < n of thread t, four scores requested at a time
+// (a loop with one LDS or L2 read per trip would wait out the read's latency on every trip).
+template <typename F>
+__device__ __forceinline__ void for_own_scores(const double* sc, int first, int n, F f) {
+  for (int j0 = first + (int)threadIdx.x; j0 < n; j0 += 4 * 256) {
+    double v[4];
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x = fmax(x, __shfl_xor(x, o));
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * 256;
+      v[u] = j < n ? sc[j] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * 256;
+      if (j < n) f(j, v[u]);
+    }
+  }
+}
+
+// Work-group (4 waves) reductions: one barrier each; every call gets LDS slots of its own (`sm`, 4
+// doubles per value) so that no barrier is needed before the slots are written.
+__device__ __forceinline__ void wg_reduce_max2(double& a, double& b, double* sm /* [8] */) {
+  a = wave_max_f64(a);
+  b = wave_max_f64(b);
   const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sm[wave] = a; sm[4 + wave] = b; }
   __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm[wave] = x;
+  a = fmax(fmax(sm[0], sm[1]), fmax(sm[2], sm[3]));
+  b = fmax(fmax(sm[4], sm[5]), fmax(sm[6], sm[7]));
+}
+
+__device__ __forceinline__ double wg_reduce_max(double x, double* sm /* [4] */) {
+  x = wave_max_f64(x);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = x;
   __syncthreads();
   return fmax(fmax(sm[0], sm[1]), fmax(sm[2], sm[3]));
 }
 
-__device__ __forceinline__ double wg_reduce_sum(double x, double* sm) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
-  const int wave = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sm[wave] = x;
+__device__ __forceinline__ double wg_reduce_sum(double x, double* sm /* [4] */) {
+  x = wave_sum_f64(x);
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = x;
   __syncthreads();
   return (sm[0] + sm[1]) + (sm[2] + sm[3]);
 }
 
-// Exclusive prefix over the 256 threads of two per-thread counts (returns totals through tg/te).
-__device__ __forceinline__ void wg_exclusive_scan2(int a, int b, int* sm /* [2][4] */, int* ea, int* eb,
-                                                   int* ta, int* tb) {
+// Exclusive prefix over the 256 threads of a per-thread count (one barrier; `sm` = 4 ints of its own).
+__device__ __forceinline__ int wg_exclusive_scan(int a, int* sm /* [4] */) {
+  const int wave = threadIdx.x >> 6;
+  const int incl = wave_inclusive_scan_i32(a);
+  if ((threadIdx.x & 63) == 63) sm[wave] = incl;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) before += (w < wave) ? sm[w] : 0;
+  return before + incl - a;
+}
+
+// Ranks, in block order, of the blocks whose bit is set: thread t holds bit u for block c0 + 256 u + t
+// (u < rows <= 32).  Calls f(u, rank) for every set bit of the calling thread and returns the number of
+// set bits of the whole work-group.  One barrier; `rowcnt` = 128 ints, not in use by anyone else until
+// the next barrier after the call.
+template <typename F>
+__device__ __forceinline__ int ordered_ranks(uint32_t bits, int rows, int* rowcnt, F f) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int ia = a, ib = b;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int xa = __shfl_up(ia, o), xb = __shfl_up(ib, o);
-    if (lane >= o) { ia += xa; ib += xb; }
+  for (int u = 0; u < rows; ++u) {
+    const unsigned long long b = __ballot((bits >> u) & 1u);
+    if (lane == 0) rowcnt[u * 4 + wave] = __popcll(b);
   }
   __syncthreads();
-  if (lane == 63) { sm[wave] = ia; sm[4 + wave] = ib; }
-  __syncthreads();
-  int oa = 0, ob = 0, sa = 0, sb = 0;
+  int run = 0;
+  for (int u0 = 0; u0 < rows; u0 += 4) {      // four rows' counts requested at a time
+    int4 c[4];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    if (w < wave) { oa += sm[w]; ob += sm[4 + w]; }
-    sa += sm[w]; sb += sm[4 + w];
+    for (int k = 0; k < 4; ++k) c[k] = reinterpret_cast<const int4*>(rowcnt)[(u0 + k) & (kMaxOwn - 1)];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int u = u0 + k;
+      if (u < rows) {                         // uniform
+        const int off = run + (wave > 0 ? c[k].x : 0) + (wave > 1 ? c[k].y : 0) + (wave > 2 ? c[k].z : 0);
+        run += (c[k].x + c[k].y) + (c[k].z + c[k].w);
+        const unsigned long long b = __ballot((bits >> u) & 1u);
+        if ((bits >> u) & 1u)
+          f(u, off + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u)));
+      }
+    }
   }
-  *ea = oa + ia - a;
-  *eb = ob + ib - b;
-  *ta = sa;
-  *tb = sb;
+  return run;
 }
 
 // SRC: 0 = scores stay in global memory (cache longer than the LDS budget), 1 = scores of the
 // score kernel are copied into LDS, 2 = fused: this kernel computes the scores itself, straight
 // into LDS (one launch, no score workspace traffic).
-template <int SRC>
-__global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
+// NT: threads per work-group while the fused form streams the cache rows (256 or 1024; the waves beyond
+// the first four end before the selection starts, which runs on 256 threads in every form).
+template <int SRC, int NT = 256>
+__global__ __launch_bounds__(NT) void seer_gate_select_kernel(GateParams p) {
+  static_assert(SRC == 2 || NT == 256, "only the fused form streams with more than four waves");
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
   __shared__ int hist[256];
   __shared__ unsigned long long mass[256];   // top-p: fixed-point probability mass per digit
   __shared__ unsigned long long mass_sel[2];
-  __shared__ int wcnt[8];
+  __shared__ int wcnt[4];
+  __shared__ __attribute__((aligned(16))) int rowcnt[4 * kMaxOwn];
   __shared__ int digit_sel[3];
-  __shared__ double red[4];
+  __shared__ double red[16];
   __shared__ int lin_hist[kLinBins];           // top-k fast path: linear-bin histogram
   __shared__ unsigned long long cand_key[kMaxCand];
   __shared__ int cand_idx[kMaxCand];
@@ -232,19 +333,26 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   const double* sc_g = p.scores + grp * p.nb_max;
 
   int S = p.seqlens[i];
+  long long k_blocks = (p.mode == 0 && p.budget_blocks) ? (long long)p.budget_blocks[i] : 0;
+  if (SRC != 0 && p.mode == 0) {        // top-k fast path state, cleared while the scores are on their way
+    for (int b = tid; b < kLinBins; b += NT) lin_hist[b] = 0;
+    if (tid == 0) cand_n = 0;
+  }
+  const double* sc = sc_g;
+  if (SRC == 1) {
+    // every score slot of the group is requested before the sequence length has arrived (one memory
+    // round trip instead of two); slots past the last full block hold whatever the workspace held and
+    // are never looked at
+    double* sl = reinterpret_cast<double*>(dyn_smem);
+    for_own_scores(sc_g, 0, p.nb_max, [&](int j, double v) { sl[j] = v; });
+    sc = sl;
+  }
   S = S < 0 ? 0 : S;
   int nfull = S / p.block_size;
   int nb = (S + p.block_size - 1) / p.block_size;
   if (nb > p.nb_max) { nb = p.nb_max; nfull = nfull < nb ? nfull : nb; }
   const bool partial = nb > nfull;
-
-  const double* sc = sc_g;
-  if (SRC == 1) {
-    double* sl = reinterpret_cast<double*>(dyn_smem);
-    for (int j = tid; j < nfull; j += 256) sl[j] = sc_g[j];
-    __syncthreads();
-    sc = sl;
-  }
+  if (SRC == 1) __syncthreads();
   if (SRC == 2) {
     // Stream the group's cache rows: 16 lanes per 256-byte row, 4 rows per wave and load, 8 loads
     // (32 KiB per work-group) per step, the next step's loads issued before the current reduction.
@@ -253,31 +361,35 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     double qd[8];
     load_gate_query(p.q_gate + grp * kHeadDim, c, qd);
     const uint16_t* base = p.kc + (int64_t)i * p.kc_stride_batch + (int64_t)h * p.kc_stride_head + c * 8;
-    uint4 kr[8], kn[8];
-    auto load_rows = [&](int j0, uint4 (&dst)[8]) {
+    constexpr int kU = NT == 1024 ? 4 : 8;       // loads in flight per lane and step
+    constexpr int kRowsPerLoad = NT / 16;        // 4 rows per wave
+    constexpr int kRowsPerStep = kU * kRowsPerLoad;
+    uint4 kr[kU], kn[kU];
+    auto load_rows = [&](int j0, uint4 (&dst)[kU]) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int j = j0 + u * 16 + wave * 4 + slot;
+      for (int u = 0; u < kU; ++u) {
+        const int jl = j0 + u * kRowsPerLoad + wave * 4 + slot;
         dst[u] = make_uint4(0, 0, 0, 0);
-        if (j < nfull) dst[u] = load_stream16(base + (int64_t)j * p.kc_stride_block);
+        if (jl < nfull) dst[u] = load_stream16(base + (int64_t)jl * p.kc_stride_block);
       }
     };
     load_rows(0, kr);
-    for (int j0 = 0; j0 < nfull; j0 += 128) {
-      const bool more = j0 + 128 < nfull;
-      if (more) load_rows(j0 + 128, kn);         // the next 128 rows are in flight during the reduction
+    for (int j0 = 0; j0 < nfull; j0 += kRowsPerStep) {
+      const bool more = j0 + kRowsPerStep < nfull;
+      if (more) load_rows(j0 + kRowsPerStep, kn);   // the next rows are in flight during the reduction
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int j = j0 + u * 16 + wave * 4 + slot;
+      for (int u = 0; u < kU; ++u) {
+        const int jl = j0 + u * kRowsPerLoad + wave * 4 + slot;
         const double sc = gate_row_score(kr[u], qd);
-        if (c == 0 && j < nfull) sl[j] = sc;
+        if (c == 0 && jl < nfull) sl[jl] = sc;
       }
       if (more) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) kr[u] = kn[u];
+        for (int u = 0; u < kU; ++u) kr[u] = kn[u];
       }
     }
     __syncthreads();
+    if (NT > 256 && tid >= 256) return;          // a barrier waits only for the waves that still run
     sc = sl;
   }
 
@@ -293,8 +405,7 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   double lin_lo = 0.0, lin_scale = 0.0;
 
   if (p.mode == 0) {
-    long long k = p.budget_blocks ? (long long)p.budget_blocks[i]
-                                  : ((long long)p.budget_tokens + p.block_size - 1) / p.block_size;
+    long long k = p.budget_blocks ? k_blocks : ((long long)p.budget_tokens + p.block_size - 1) / p.block_size;
     k = k < 0 ? 0 : k;
     k = k > nb ? nb : k;
     k = k > p.max_sel ? p.max_sel : k;
@@ -313,24 +424,19 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
       // every block in a higher bin is selected, and the few blocks inside the boundary bin are
       // ranked exactly (key, then lower index) against each other.  Falls through to the radix
       // walk when that bin is crowded (many equal or nearly equal scores).
-      double lo = INFINITY, hi = -INFINITY;
-      for (int j = tid; j < nfull; j += 256) { const double v = sc[j]; lo = fmin(lo, v); hi = fmax(hi, v); }
-      hi = wg_reduce_max(hi, red);
-      lo = -wg_reduce_max(-lo, red);
+      double hi = -INFINITY, nlo = -INFINITY;
+      for_own_scores(sc, 0, nfull, [&](int, double v) { hi = fmax(hi, v); nlo = fmax(nlo, -v); });
+      wg_reduce_max2(hi, nlo, red + 8);     // (lin_hist and cand_n were cleared before the scores arrived)
+      const double lo = -nlo;
       const double scale = __ddiv_rn((double)kLinBins, __dsub_rn(hi, lo));
       if (hi > lo && scale > 0.0 && scale < 1.0e300) {
-        for (int b = tid; b < kLinBins; b += 256) lin_hist[b] = 0;
-        if (tid == 0) cand_n = 0;
         unsigned char* flags = dyn_smem + (size_t)p.nb_max * sizeof(double);
-        for (int j = tid; j < nfull; j += 256) flags[j] = 0;
-        __syncthreads();
-        for (int j = tid; j < nfull; j += 256) atomicAdd(&lin_hist[lin_bin_of(sc[j], lo, scale)], 1);
+        for_own_scores(sc, 0, nfull, [&](int, double v) { atomicAdd(&lin_hist[lin_bin_of(v, lo, scale)], 1); });
         __syncthreads();
         // thread t owns bins 1023-4t .. 1020-4t (descending); exclusive scan of the counts from the top
         const int b0 = kLinBins - 1 - 4 * tid;
         const int c0 = lin_hist[b0], c1 = lin_hist[b0 - 1], c2 = lin_hist[b0 - 2], c3 = lin_hist[b0 - 3];
-        int above, dummy_e, tot, dummy_t;
-        wg_exclusive_scan2(c0 + c1 + c2 + c3, 0, wcnt, &above, &dummy_e, &tot, &dummy_t);
+        int above = wg_exclusive_scan(c0 + c1 + c2 + c3, wcnt);
         if (above < from_full && from_full <= above + c0 + c1 + c2 + c3) {   // exactly one thread
           int bsel = b0, cnt = c0;
           if (from_full > above + c0) {
@@ -348,16 +454,15 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
         lin_sel = digit_sel[0];
         const int need = digit_sel[1], cnt = digit_sel[2];
         if (cnt <= kMaxCand) {
-          for (int j = tid; j < nfull; j += 256) {
-            const double v = sc[j];
+          for_own_scores(sc, 0, nfull, [&](int j, double v) {
             if (lin_bin_of(v, lo, scale) == lin_sel) {
               const int at = atomicAdd(&cand_n, 1);
               cand_key[at] = score_key(v);
               cand_idx[at] = j;
             }
-          }
+          });
           __syncthreads();
-          if (tid < cnt) {
+          if (tid < cnt) {        // every block of the boundary bin gets its flag written: taken or not
             const unsigned long long mk = cand_key[tid];
             const int mi = cand_idx[tid];
             int rank = 0;
@@ -365,14 +470,12 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
               const unsigned long long uk = cand_key[u];
               rank += (uk > mk) || (uk == mk && cand_idx[u] < mi);
             }
-            if (rank < need) flags[mi] = 1;
+            flags[mi] = rank < need ? 1 : 0;
           }
           __syncthreads();
           lin_lo = lo;
           lin_scale = scale;
           lin_fast = true;
-        } else {
-          __syncthreads();
         }
       }
     }
@@ -393,12 +496,7 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
           const int d0 = 255 - 4 * lane;
           const int c0 = hist[d0], c1 = hist[d0 - 1], c2 = hist[d0 - 2], c3 = hist[d0 - 3];
           const int own = c0 + c1 + c2 + c3;
-          int incl = own;
-#pragma unroll
-          for (int o = 1; o < 64; o <<= 1) {
-            const int x = __shfl_up(incl, o);
-            if (lane >= o) incl += x;
-          }
+          const int incl = wave_inclusive_scan_i32(own);
           int above = incl - own;                     // candidates with a digit above d0
           if (above < remaining && remaining <= incl) {   // true for exactly one lane
             int dsel = d0, cnt = c0;
@@ -428,11 +526,11 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
   } else {
     if (nfull > 0) {
       double mx = -INFINITY;
-      for (int j = tid; j < nfull; j += 256) mx = fmax(mx, __dmul_rn(sc[j], p.inv_sqrt_dg));
+      for_own_scores(sc, 0, nfull, [&](int, double v) { mx = fmax(mx, __dmul_rn(v, p.inv_sqrt_dg)); });
       m = wg_reduce_max(mx, red);
       double z = 0.0;
-      for (int j = tid; j < nfull; j += 256) z += exp(__dsub_rn(__dmul_rn(sc[j], p.inv_sqrt_dg), m));
-      Z = wg_reduce_sum(z, red);
+      for_own_scores(sc, 0, nfull, [&](int, double v) { z += exp(__dsub_rn(__dmul_rn(v, p.inv_sqrt_dg), m)); });
+      Z = wg_reduce_sum(z, red + 4);
     }
     if (p.mode == 2 && nfull > 0) {
       // Top-p: the same radix walk as top-k, but steered by probability mass instead of counts.
@@ -518,15 +616,11 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
     }
   }
 
-  // ---- ordered compaction: thread t owns block ids [t*run, (t+1)*run) -----------------------
+  // ---- ordered compaction: thread t owns blocks t, t + 256, ... (8192 blocks per pass) -------------
   const bool any_full = (p.mode == 0) ? (from_full > 0) : (nfull > 0);
   int n = 0;
   if (any_full) {
-    const int run = ((nfull + 255) / 256) | 1;   // odd run length: consecutive threads then start in different LDS banks
-    const int j0 = tid * run;
-    const int j1 = (j0 + run < nfull) ? j0 + run : nfull;
-    auto classify = [&](int j, bool* gt, bool* eq) {
-      const double s = sc[j];
+    auto classify = [&](int j, double s, bool* gt, bool* eq) {
       if (lin_fast) {
         const int b = lin_bin_of(s, lin_lo, lin_scale);
         const unsigned char* flags = dyn_smem + (size_t)p.nb_max * sizeof(double);
@@ -542,28 +636,33 @@ __global__ __launch_bounds__(256) void seer_gate_select_kernel(GateParams p) {
         *eq = false;
       }
     };
-    int cg = 0, ce = 0;
-    for (int j = j0; j < j1; ++j) {
-      bool gt, eq;
-      classify(j, &gt, &eq);
-      cg += gt;
-      ce += eq;
-    }
-    int og, oe, tg, te;
-    wg_exclusive_scan2(cg, ce, wcnt, &og, &oe, &tg, &te);
-    int eq_seen = oe;
-    int pos = og + (oe < need_eq ? oe : need_eq);
-    for (int j = j0; j < j1; ++j) {
-      bool gt, eq;
-      classify(j, &gt, &eq);
-      const bool take = gt || (eq && eq_seen < need_eq);
-      eq_seen += eq;
-      if (take) {
-        if (pos < p.max_sel) out[pos] = j;
-        ++pos;
+    int eq_before = 0;
+    for (int c0 = 0; c0 < nfull; c0 += 256 * kMaxOwn) {
+      const int left = nfull - c0;
+      const int rows = left >= 256 * kMaxOwn ? kMaxOwn : (left + 255) >> 8;
+      uint32_t take = 0, ties = 0;
+      const int c1 = c0 + rows * 256 < nfull ? c0 + rows * 256 : nfull;
+      for_own_scores(sc, c0, c1, [&](int j, double v) {
+        bool gt, eq;
+        classify(j, v, &gt, &eq);
+        const int u = (j - c0) >> 8;
+        take |= (uint32_t)gt << u;
+        ties |= (uint32_t)eq << u;
+      });
+      if (need_eq > 0) {      // blocks that tie with the k-th score: the first need_eq of them in block order
+        uint32_t add = 0;
+        const int tot = ordered_ranks(ties, rows, rowcnt, [&](int u, int r) { if (eq_before + r < need_eq) add |= 1u << u; });
+        eq_before += tot;
+        take |= add;
+        __syncthreads();      // rowcnt is written again below
       }
+      const int base = n;
+      n += ordered_ranks(take, rows, rowcnt, [&](int u, int r) {
+        const int pos = base + r;
+        if (pos < p.max_sel) out[pos] = c0 + u * 256 + tid;
+      });
+      if (c0 + 256 * kMaxOwn < nfull) __syncthreads();   // the next pass rewrites rowcnt
     }
-    n = tg + (te < need_eq ? te : need_eq);
   }
   n = n < p.max_sel ? n : p.max_sel;
   if (force_last && n < p.max_sel) {
@@ -621,12 +720,20 @@ hipError_t launch_gate_select(const GateParams& p, hipStream_t s) {
 }
 
 bool gate_fused_possible(const GateParams& p) {
-  return p.nb_max <= kSelectLdsBlocks && reserve_dyn_lds(seer_gate_select_kernel<2>, select_dyn_lds(p.nb_max));
+  const size_t dyn = select_dyn_lds(p.nb_max);
+  return p.nb_max <= kSelectLdsBlocks && reserve_dyn_lds(seer_gate_select_kernel<2, 256>, dyn) &&
+         reserve_dyn_lds(seer_gate_select_kernel<2, 1024>, dyn);
 }
 
+// Caches of 512 blocks and more are streamed by 16 waves per group (one wave reads 4 rows per load, so
+// shorter caches would leave most of them without rows), the rest by 4.
 hipError_t launch_gate_fused(const GateParams& p, hipStream_t s) {
   dim3 grid(p.Hkv, p.B);
-  hipLaunchKernelGGL(seer_gate_select_kernel<2>, grid, dim3(256), select_dyn_lds(p.nb_max), s, p);
+  const size_t dyn = select_dyn_lds(p.nb_max);
+  if (p.nb_max >= 512)
+    hipLaunchKernelGGL((seer_gate_select_kernel<2, 1024>), grid, dim3(1024), dyn, s, p);
+  else
+    hipLaunchKernelGGL((seer_gate_select_kernel<2, 256>), grid, dim3(256), dyn, s, p);
   return hipGetLastError();
 }
 
