@@ -242,7 +242,7 @@ class Bench:
                          "split_kernel_us": split, "merge_kernel_us": merge,
                          "frac_split_kernel_alone": ab["decode"] / (split["mean"] * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                          "frac_at_min_duration": ab["decode"] / ((split["min"] + (merge["min"] if merge else 0.0)) * 1e-6) / 1e9 / HBM_PEAK_GBPS},
-            "gate_roofline": {"bound": "hbm", "kernel": "seer_gate_score + seer_gate_select",
+            "gate_roofline": {"bound": "hbm", "kernel": "seer_gate_score + seer_gate_select" if kern["gate_score"] else "seer_gate_select (fused: scores and selection)",
                               "achieved": ab["gate"] / (gate_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": ab["gate"] / (gate_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
                               "traffic": committed_traffic(self.w.name, "gate_bytes") if self.mode == self.seer.SELECT_TOPK else None,

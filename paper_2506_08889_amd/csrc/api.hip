@@ -346,15 +346,14 @@ seer_status seer_gate_select(const void* q_gate, const void* kc_cache, int64_t k
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   // The fused kernel (one work-group per group computes its scores straight into LDS, then selects)
-  // saves a launch and the score workspace and is the faster form up to mid-size caches (measured,
-  // step of gate + decode: batch 16 x 32k tokens 58.8 vs 59.9 us, batch 32 x 8k-64k tokens at block 128 106.7 vs
-  // 109.4 us).  At scale a wide score kernel (every CU streams cache rows from the first microsecond)
-  // followed by the select kernel wins: a batch of 64 x 128k-token caches has exactly two groups per
-  // CU, all of which finish streaming and then select at the same time (step 580 vs 558 us).
-  bool fused = seer::gate_fused_possible(p) && (size_t)B * Hkv * nb_max * Dg * 2 <= ((size_t)128 << 20);
+  // saves a launch and the score workspace and is the faster form wherever a group's scores fit into
+  // LDS (measured in one process, step of gate + decode, fused vs score kernel + select kernel: batch
+  // 16 x 32k tokens 59.0 vs 60.6 us; batch 32 x 8k-64k tokens at block 128 105.8 vs 109.0 us; batch
+  // 128 x 4k-128k tokens 376 vs 382 us; batch 64 x 128k tokens 560.4 vs 562.2 us).  Longer caches take
+  // the wide score kernel (every CU streams cache rows) followed by the select kernel.
+  bool fused = seer::gate_fused_possible(p);
   const int gate_impl = g_knob_gate.load(std::memory_order_relaxed);
   if (gate_impl == 1) fused = false;
-  if (gate_impl == 2) fused = seer::gate_fused_possible(p);
   if (fused) {
     Timed t(SEER_KERNEL_GATE_SELECT, s);
     e = seer::launch_gate_fused(p, s);
