@@ -425,7 +425,7 @@ def main_workload(args, seer, synth, torch, np):
         "multi_token_decode": multi,
         "training_forward": train,
         "dense": res.get("dense"), "speedup_vs_dense": res.get("speedup_vs_dense"),
-        "paper_context": "paper: up to 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware, not a target)",
+        "paper_context": "the paper measures about 9x over FlashAttention-3 at 90% sparsity on H100 (other hardware: context, not a target)",
     }
 
     # ---- CPU oracle on a bounded sample of the same workload: the reported baseline, and a parity check
