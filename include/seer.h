@@ -303,7 +303,8 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope /* host struct */, const
  * T tokens per sequence; out [B,T,Hq,d] of out_dtype; lse fp32 [B,T,Hq] (may be NULL);
  * gt fp32 [B,Hkv,T,ceil(T/block_size)].  block_size in {16, 32, 64, 128}, d = 128, g in 1..8, scale > 0
  * (SEER_ERR_UNSUPPORTED otherwise).
- * Workspace: seer_attn_ground_truth_workspace_bytes.
+ * Workspace: seer_attn_ground_truth_workspace_bytes (the block maxima of the rows that can see a block,
+ * i.e. about half of B*Hq*ceil(T/block_size)*T floats, plus one log-sum-exp per row and head).
  */
 seer_status seer_attn_ground_truth_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int block_size,
                                                    size_t* bytes /* host, out */);

@@ -520,8 +520,14 @@ seer_status seer_kc_update(const seer_kv_layout* k_nope, const void* wk, const f
 }
 
 static size_t attn_gt_ws_bytes(int B, int T, int Hq, int block_size) {
-  const size_t nb = (size_t)(T + block_size - 1) / block_size, Tp = ((size_t)T + 15) / 16 * 16;
-  return align_up((size_t)B * Hq * nb * Tp * sizeof(float), 256) + align_up((size_t)B * Hq * T * sizeof(float), 256);
+  const int64_t nb = ((int64_t)T + block_size - 1) / block_size, Tp = ((int64_t)T + 15) / 16 * 16;
+  return align_up((size_t)B * Hq * (size_t)seer::raw_head_elems(nb, Tp, block_size) * sizeof(float), 256) +
+         align_up((size_t)B * Hq * T * sizeof(float), 256);
+}
+// The finalize kernel addresses one head's block maxima with 32-bit offsets.
+static bool attn_gt_rows_fit(int T, int block_size) {
+  const double nb = ((double)T + block_size - 1) / block_size;
+  return nb * ((double)T + 16) < 2147483648.0;
 }
 static bool attn_gt_sizes_ok(int B, int T, int Hq, int Hkv, seer_status* why) {
   if (B <= 0 || T <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) { *why = SEER_ERR_SHAPE; return false; }
@@ -537,7 +543,7 @@ seer_status seer_attn_ground_truth_workspace_bytes(int B, int T, int Hq, int Hkv
   seer_status why;
   if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
   if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
-      !block_size_ok(block_size))
+      !block_size_ok(block_size) || !attn_gt_rows_fit(T, block_size))
     return SEER_ERR_UNSUPPORTED;
   *bytes = attn_gt_ws_bytes(B, T, Hq, block_size);
   return SEER_OK;
@@ -552,7 +558,7 @@ seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv, cons
   seer_status why;
   if (!attn_gt_sizes_ok(B, T, Hq, Hkv, &why)) return why;
   if (d != seer::kHeadDim || Hq / Hkv > seer::kMaxGroup ||
-      !block_size_ok(block_size))
+      !block_size_ok(block_size) || !attn_gt_rows_fit(T, block_size))
     return SEER_ERR_UNSUPPORTED;
   if (kv->page_table) return SEER_ERR_UNSUPPORTED;      // whole-sequence training batches are contiguous
   if (!(scale > 0.f) || scale > 3.0e38f) return SEER_ERR_UNSUPPORTED;   // row maxima are taken before scaling
@@ -578,7 +584,7 @@ seer_status seer_attn_ground_truth(const void* q, const seer_kv_layout* kv, cons
   p.scale_log2e = (float)((double)scale * 1.4426950408889634);
   p.raw = static_cast<float*>(workspace);
   p.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) +
-                                    align_up((size_t)B * Hq * p.nb * p.Tp * sizeof(float), 256));
+                                    align_up((size_t)B * Hq * (size_t)seer::raw_head_elems(p.nb, p.Tp, block_size) * sizeof(float), 256));
   p.out = out;
   p.lse = lse;
   p.gt = gt;

@@ -88,15 +88,28 @@ struct TrainFwdParams {
   int64_t stride_seq, stride_head, stride_token;
   const int32_t* seqlens;       // [B] or nullptr
   int32_t B, T, Hq, Hkv, g, block_size, nb;
-  int32_t Tp;                   // T rounded up to a multiple of 16: row stride of raw
+  int32_t Tp;                   // T rounded up to a multiple of 16
   float scale_log2e;
-  float* raw;                   // [B,Hq,nb,Tp] block maxima of the base-2 logits of every query row
+  float* raw;                   // per (sequence, head): block maxima of the base-2 logits, block-major and
+                                // triangular - block j holds rows j*block_size .. Tp-1 (see raw_block_offset)
   float* lse2;                  // [B,Hq,T] base-2 log-sum-exp of every query row
   void* out;                    // [B,T,Hq,128]
   float* lse;                   // [B,T,Hq] or nullptr
   float* gt;                    // [B,Hkv,T,nb]
   int32_t out_is_f32;
 };
+
+// Layout of TrainFwdParams::raw for one (sequence, head).  A query row sees block j only from row
+// j*block_size on, so block j stores rows j*bs .. Tp-1 (Tp - j*bs floats, a multiple of 16) and the
+// blocks follow each other: half the footprint of a full [nb][Tp] rectangle.
+__host__ __device__ inline int64_t raw_block_offset(int64_t j, int64_t Tp, int64_t bs) {
+  return j * Tp - bs * (j * (j - 1) / 2);
+}
+__host__ __device__ inline int64_t raw_head_elems(int64_t nb, int64_t Tp, int64_t bs) { return raw_block_offset(nb, Tp, bs); }
+// element of (block j, row q), q >= j*bs
+__host__ __device__ inline int64_t raw_index(int64_t j, int64_t q, int64_t Tp, int64_t bs) {
+  return raw_block_offset(j, Tp, bs) + (q - j * bs);
+}
 
 // Launchers (each returns the hipError_t of the launch).
 hipError_t launch_attn_fwd(const TrainFwdParams& p, hipStream_t s);

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): the fills have landed
   __syncthreads();
 
-  float* rawbase = p.raw + ((int64_t)i * p.Hq + h) * p.nb * (int64_t)p.Tp;
+  float* rawbase = p.raw + ((int64_t)i * p.Hq + h) * raw_head_elems(p.nb, p.Tp, p.block_size);
 
   // One 64-key tile for this wave.  MASKED: the tile may hold keys beyond some row of the wave (only
   // the last tile or two of a wave's range); interior tiles carry no masking code at all.
@@ -227,18 +227,20 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const int j = (kt0 >> 4) + t;
-            if (q4 == 0 && qrow[a] < p.T && j < p.nb) rawbase[(int64_t)j * p.Tp + qrow[a]] = mx * p.scale_log2e;
+            if (q4 == 0 && qrow[a] < p.T && j < p.nb && j * 16 <= qrow[a])     // only blocks the row can see have a slot
+              rawbase[raw_index(j, qrow[a], p.Tp, 16)] = mx * p.scale_log2e;
           }
         } else if (p.block_size == 32) {
           if (q4 == 0 && qrow[a] < p.T) {
             const int j0 = kt0 >> 5;
-            rawbase[(int64_t)j0 * p.Tp + qrow[a]] = mh[0];
-            if (j0 + 1 < p.nb) rawbase[(int64_t)(j0 + 1) * p.Tp + qrow[a]] = mh[1];
+            if (j0 * 32 <= qrow[a]) rawbase[raw_index(j0, qrow[a], p.Tp, 32)] = mh[0];
+            if (j0 + 1 < p.nb && (j0 + 1) * 32 <= qrow[a]) rawbase[raw_index(j0 + 1, qrow[a], p.Tp, 32)] = mh[1];
           }
         } else {
           const float mt = fmaxf(mh[0], mh[1]);
           bmax[a] = (kt0 % p.block_size) == 0 ? mt : fmaxf(bmax[a], mt);
-          if (q4 == 0 && qrow[a] < p.T) rawbase[(int64_t)(kt0 / p.block_size) * p.Tp + qrow[a]] = bmax[a];
+          // (a wave only works on tiles that start at or before its rows, so the row sees this block)
+          if (q4 == 0 && qrow[a] < p.T) rawbase[raw_index(kt0 / p.block_size, qrow[a], p.Tp, p.block_size)] = bmax[a];
         }
 
         const float m_new = fmaxf(m_run[a], fmaxf(mh[0], mh[1]));
@@ -367,7 +369,8 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
 #pragma unroll
   for (int hh = 0; hh < kMaxGroup; ++hh)
     l2[hh] = (hh < g && real) ? p.lse2[((int64_t)i * p.Hq + hk * g + hh) * p.T + t] : 0.f;
-  const float* raw0 = p.raw + ((int64_t)i * p.Hq + (int64_t)hk * g) * p.nb * (int64_t)p.Tp;
+  const int64_t head_elems = raw_head_elems(p.nb, p.Tp, p.block_size);
+  const float* raw0 = p.raw + ((int64_t)i * p.Hq + (int64_t)hk * g) * head_elems;
   // N blocks at once for this row: every load is issued (index clamped) before the first exponential,
   // so a thread keeps N * g reads in flight; blocks the row cannot see give 0.
   auto block_probs = [&](auto n_tag, const int (&js)[decltype(n_tag)::value], float (&out)[decltype(n_tag)::value]) {
@@ -376,9 +379,11 @@ __global__ __launch_bounds__(256) void seer_gt_finalize_kernel(TrainFwdParams p)
 #pragma unroll
     for (int u = 0; u < N; ++u) {
       const int j = js[u] < nvis ? js[u] : 0;
+      // 32-bit arithmetic: one head's slice holds fewer than 2^31 floats (checked on the host)
+      const int at = j * p.Tp - p.block_size * (j * (j - 1) / 2) + (t - j * p.block_size);
 #pragma unroll
       for (int hh = 0; hh < kMaxGroup; ++hh)
-        x[u][hh] = (hh < g && real) ? raw0[((int64_t)hh * p.nb + j) * p.Tp + t] : -INFINITY;
+        x[u][hh] = (hh < g && real) ? raw0[hh * head_elems + at] : -INFINITY;
     }
 #pragma unroll
     for (int u = 0; u < N; ++u) {
