@@ -655,7 +655,7 @@ def paper_sweep(args, seer, synth, torch):
                 k, v = caches[i % copies]
                 seer.dense_decode(q, k, v, seqlens, nb, bs, scale, out=out, lse=lse, workspace=ws)
 
-            t_dense = kernel_us(dense, max(4, args.steps // 2))
+            t_dense = kernel_us(dense, max(4, min(args.steps, 30) // 2))
             dense_gbps = kv_bytes / (t_dense * 1e-6) / 1e9
             for sp in (0.5, 0.75, 0.9):
                 k_sel = max(1, round(nb * (1 - sp)))
@@ -668,7 +668,7 @@ def paper_sweep(args, seer, synth, torch):
                     seer.sparse_decode(q, k, v, seqlens, idx, cnt, bs, scale, out=out, lse=lse, workspace=ws)
 
                 time.sleep(0.2)
-                t_sp = kernel_us(sparse, args.steps)
+                t_sp = kernel_us(sparse, min(args.steps, 30))
                 sel_bytes = B * Hkv * k_sel * bs * d * 2 * 2
                 print(f"| {S} | {B} | {sp} | {k_sel} of {nb} | {t_dense:.1f} | {dense_gbps:.0f} | {t_sp:.1f} | "
                       f"{sel_bytes / (t_sp * 1e-6) / 1e9:.0f} | {t_dense / t_sp:.2f}x | {nb / k_sel:.2f}x |", flush=True)
@@ -679,8 +679,8 @@ def paper_sweep(args, seer, synth, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--rotate", type=int, default=4, help="independent query sets cycled through the steps")
     ap.add_argument("--kv-copies", type=int, default=0, help="independent KV caches cycled (0 = auto)")
