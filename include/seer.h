@@ -248,7 +248,7 @@ seer_status seer_gate_q(const void* q_nope, const void* wq, const float* rope_co
 /*
  * AttnGate from the raw query (Eq. 1a followed by Eq. 1c and the selection of Sec. 3.1): what
  * seer_gate_q followed by seer_gate_select computes, as one call of a decode step.  The gate query of
- * every (sequence, kv head) is made once by a small kernel in front of the score kernel and kept in
+ * every (sequence, kv head) is made once by a small kernel in front of the gate kernel(s) and kept in
  * the workspace; pass q_gate_out (bf16 [B,Hkv,Dg], device) to receive it, or NULL.  Arguments as in
  * the two calls; the workspace is the one of seer_gate_select (seer_gate_workspace_bytes covers both).
  * All host-visible argument errors of both calls are reported before anything is launched.
@@ -330,8 +330,9 @@ seer_status seer_hbm_read_probe(const void* src, size_t bytes, void* sink, void*
  * Unknown knobs return SEER_ERR_UNSUPPORTED.
  *   SEER_KNOB_DECODE_IMPL    0 = auto, 1 = VALU kernel, 2 = MFMA kernel
  *   SEER_KNOB_DECODE_SPLITS  0 = auto, n > 0 = force n splits of the block list
- *   SEER_KNOB_GATE_IMPL      0 = auto, 1 = score kernel + select kernel, 2 = one fused kernel
- *                            (when the cache has at most 8192 blocks per sequence)
+ *   SEER_KNOB_GATE_IMPL      0 = auto (one fused kernel when the cache has at most 8192 blocks per
+ *                            sequence, else score kernel + select kernel), 1 = score kernel + select
+ *                            kernel, 2 = same as 0
  */
 typedef enum seer_knob {
   SEER_KNOB_DECODE_IMPL = 0,
