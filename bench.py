@@ -530,6 +530,29 @@ def also_workload(args, name, seer, synth, torch):
     return out
 
 
+def graph_replay_us(b, torch, n):
+    """One step (query set 0, cache 0) captured into a HIP graph on a stream of its own and replayed n
+    times back to back: what a serving loop that replays its decode step pays per step, in us.  The
+    library records no memset and allocates nothing, so the capture holds only its kernels."""
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        b.step(0)                                   # warm-up on the capture stream
+        s.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            b.step(0)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        g.replay()
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(n):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t) * 1e6 / n
+
+
 def c1_latency(args, seer, synth, torch):
     """The tiny configuration is latency-bound (1 MiB of selected KV): microseconds per step, once with
     128 KV caches cycled (cold: 512 MiB between re-uses, beyond the memory-side cache and the L2s) and once
@@ -548,9 +571,12 @@ def c1_latency(args, seer, synth, torch):
         out[label] = {"step_us_launch_inclusive_mean": ms * 1e3, "step_us_gpu_events": ev,
                       "kernels_us": {k: ({"mean": v["mean"], "median": v["median"], "min": v["min"]} if v else None)
                                      for k, v in kern.items()}}
+        if copies == 1:
+            out[label]["step_us_graph_replay_mean"] = graph_replay_us(b, torch, n)
         out["workload"] = b.describe()
         b.release()
-    log(f"[bench] c1: cold {out['cold_rotated']['step_us_launch_inclusive_mean']:.1f} us, warm {out['warm']['step_us_launch_inclusive_mean']:.1f} us")
+    log(f"[bench] c1: cold {out['cold_rotated']['step_us_launch_inclusive_mean']:.1f} us, warm {out['warm']['step_us_launch_inclusive_mean']:.1f} us, "
+        f"warm under graph replay {out['warm']['step_us_graph_replay_mean']:.1f} us")
     return out
 
 

@@ -53,8 +53,10 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // (~0.8 us each), so short lists are only cut when the slices save more than the merge costs.
 // A slice has at least 4 list entries.
 // Lists of very different lengths (SEER_HINT_RAGGED_LISTS) get slices of about 2048 tokens so
-// that the longest list is spread over many work-groups; equal-length lists lose ~5 % to that,
-// hence the opt-in.  (Measured on batch 128 with mixed lengths, a work-group pays about 3 us for every
+// that the longest list is spread over many work-groups (about 1000 when the batch is small: batch 32
+// with 8 k-64 k-token sequences at block 128 runs its split kernel in 88 us with 7-block slices against
+// 92 us with 13-block ones, while batch 128 gets slower below 2048); equal-length lists lose ~5 % to
+// slicing, hence the opt-in.  (Measured on batch 128 with mixed lengths, a work-group pays about 3 us for every
 // slice it starts: slices of 512 / 1024 / 2048 / 4096 tokens give 73 / 77 / 80 / 82 % of the HBM peak
 // at 50 % sparsity and 67 / 70 / 70-73 / 67-68 % at 95 %, where long slices no longer balance.)
 constexpr long kMinSliceBlocks = 4;    // at least one block per wave of a work-group
@@ -83,7 +85,12 @@ void plan_splits(int B, int Hkv, int max_blocks, int block_size, bool ragged, in
       if (saved < 6.5) ns = 1;
     }
     if (ragged) {
-      long len_r = 2048 / block_size;
+      // about 2048 tokens per slice; shorter (down to 768) when the whole batch holds only a few slices
+      // per resident work-group, so that a launch of two or three units per slot still ends evenly
+      const double per_slot = (double)groups * max_blocks * block_size / (2.0 * (double)slots);   // upper bound
+      long tok = (long)(per_slot / 3.0);
+      tok = tok < 768 ? 768 : (tok > 2048 ? 2048 : tok);
+      long len_r = tok / block_size;
       if (len_r < kMinSliceBlocks) len_r = kMinSliceBlocks;
       const long ns_r = (max_blocks + len_r - 1) / len_r;
       if (ns_r > ns) ns = ns_r;
