@@ -705,8 +705,8 @@ def paper_sweep(args, seer, synth, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--rotate", type=int, default=4, help="independent query sets cycled through the steps")
     ap.add_argument("--kv-copies", type=int, default=0, help="independent KV caches cycled (0 = auto)")
@@ -723,7 +723,7 @@ def main():
     ap.add_argument("--also", default="c2,c3,c1,c5",
                     help="further workloads reported compactly in the same line, comma-separated ('' = none); "
                          "c1 = latency entry, c5 = the selection-mode / sparsity sweep")
-    ap.add_argument("--sweep-steps", type=int, default=10, help="timed steps per point of the c5 sweep")
+    ap.add_argument("--sweep-steps", type=int, default=40, help="timed steps per point of the c5 sweep")
     ap.add_argument("--sweep-blocks", default="64,128")
     ap.add_argument("--sweep-keep", default="0.5,0.25,0.1,0.05")
     ap.add_argument("--print-sources-hash", action="store_true", help="print the kernel-source fingerprint and exit")
