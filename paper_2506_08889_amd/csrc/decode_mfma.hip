@@ -456,8 +456,8 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 //   Then every work-group derives the same table of the remaining units from the groups' counts:
 //     [0, G - W)   first slices of the groups W .. G-1 (when there are more groups than work-groups),
 //     then         the further slices of full length of all groups, in group order,
-//     then         the shorter last slices, first those at least half as long, then the rest - so the
-//                  launch ends on its shortest units.
+//     then         the shorter last slices in four classes by length (at least 3/4, 1/2, 1/4 of a full
+//                  slice, then the rest) - so the launch ends on its shortest units.
 //   Units are handed out through a counter in the workspace - whichever work-group is free takes the
 //   next one, so compute units that get less of the memory system take fewer - or, when the counter
 //   does not hold a valid state (first use of a workspace), round-robin.  The partial result of a unit
@@ -469,9 +469,10 @@ template <bool ROWS128, bool B16>
 __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSliceLdsBytes];
   __shared__ int pfx_full[kMaxPersistGroups + 1];   // exclusive prefix of the groups' full-length slices after the first
-  __shared__ int pfx_rem[kMaxPersistGroups + 1];    // ... of their shorter last slices after the first that hold >= L/2 entries
-  __shared__ int pfx_tail[kMaxPersistGroups + 1];   // ... and of those that hold fewer (0 or 1 each): the launch ends on these
-  __shared__ int wsum[3][4];
+  // ... and of their shorter last slices after the first, by length class c = floor(4 * entries / L)
+  // (0 or 1 per group and class, so 16 bits hold any prefix)
+  __shared__ unsigned short pfx_rem[4][kMaxPersistGroups + 1];
+  __shared__ int wsum[5][4];
   __shared__ int s_next, s_dynamic;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -497,7 +498,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
   {
     const int per = (G + 255) / 256;
     const int g0 = tid * per;
-    int f_sum = 0, r_sum = 0, t_sum = 0;
+    int f_sum = 0, r_sum[4] = {0, 0, 0, 0};
     for (int u = 0; u < per; ++u) {
       const int grp = g0 + u;
       if (grp >= G) break;
@@ -512,35 +513,54 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
         n = nb < p.max_blocks ? nb : p.max_blocks;
       }
       const int full = n / L, rest = n % L;
+      const int cls = (full > 0 && rest != 0) ? (4 * rest) / L : -1;
       pfx_full[grp] = f_sum;                  // local exclusive prefix, made global below
-      pfx_rem[grp] = r_sum;
-      pfx_tail[grp] = t_sum;
       f_sum += full > 0 ? full - 1 : 0;
-      r_sum += (full > 0 && rest != 0 && 2 * rest >= L) ? 1 : 0;
-      t_sum += (full > 0 && rest != 0 && 2 * rest < L) ? 1 : 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        pfx_rem[c][grp] = (unsigned short)r_sum[c];
+        r_sum[c] += cls == c ? 1 : 0;
+      }
     }
-    int fi = f_sum, ri = r_sum, ti = t_sum;   // inclusive scan over the threads
+    int fi = f_sum, ri[4] = {r_sum[0], r_sum[1], r_sum[2], r_sum[3]};   // inclusive scan over the threads
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-      const int xf = __shfl_up(fi, o), xr = __shfl_up(ri, o), xt = __shfl_up(ti, o);
-      if (lane >= o) { fi += xf; ri += xr; ti += xt; }
+      const int xf = __shfl_up(fi, o);
+      int xr[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) xr[c] = __shfl_up(ri[c], o);
+      if (lane >= o) {
+        fi += xf;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ri[c] += xr[c];
+      }
     }
     __syncthreads();                          // round 0 is done with its LDS; wsum is free
-    if (lane == 63) { wsum[0][wave] = fi; wsum[1][wave] = ri; wsum[2][wave] = ti; }
+    if (lane == 63) {
+      wsum[0][wave] = fi;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) wsum[1 + c][wave] = ri[c];
+    }
     __syncthreads();
-    int fo = fi - f_sum, ro = ri - r_sum, to = ti - t_sum;
-    for (int ww = 0; ww < wave; ++ww) { fo += wsum[0][ww]; ro += wsum[1][ww]; to += wsum[2][ww]; }
+    int fo = fi - f_sum, ro[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) ro[c] = ri[c] - r_sum[c];
+    for (int ww = 0; ww < wave; ++ww) {
+      fo += wsum[0][ww];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) ro[c] += wsum[1 + c][ww];
+    }
     for (int u = 0; u < per; ++u) {
       const int grp = g0 + u;
       if (grp >= G) break;
       pfx_full[grp] += fo;
-      pfx_rem[grp] += ro;
-      pfx_tail[grp] += to;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) pfx_rem[c][grp] = (unsigned short)(pfx_rem[c][grp] + ro[c]);
     }
     if (tid == 255) {
       pfx_full[G] = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-      pfx_rem[G] = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
-      pfx_tail[G] = wsum[2][0] + wsum[2][1] + wsum[2][2] + wsum[2][3];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) pfx_rem[c][G] = (unsigned short)(wsum[1 + c][0] + wsum[1 + c][1] + wsum[1 + c][2] + wsum[1 + c][3]);
     }
     if (tid == 0) {
       const bool valid = p.sched && (uint32_t)(took >> 32) + (uint32_t)took == kSchedMagic;
@@ -550,7 +570,9 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
     __syncthreads();
   }
   const int first_more = G > W ? G - W : 0;   // first slices that round 0 did not cover
-  const int UF = pfx_full[G], UR = pfx_rem[G], D = first_more + UF + UR + pfx_tail[G];
+  const int UF = pfx_full[G];
+  const int UR3 = pfx_rem[3][G], UR2 = pfx_rem[2][G], UR1 = pfx_rem[1][G], UR0 = pfx_rem[0][G];
+  const int D = first_more + UF + UR3 + UR2 + UR1 + UR0;
   const bool dynamic = s_dynamic != 0;
   int d = s_next;
   __syncthreads();
@@ -561,19 +583,28 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
       grp = W + d;
       split = 0;
     } else {
-      const int k = d - first_more;
-      const bool is_full = k < UF;
-      const int* pfx = is_full ? pfx_full : (k < UF + UR ? pfx_rem : pfx_tail);
-      const int key = is_full ? k : (k < UF + UR ? k - UF : k - UF - UR);
+      int key = d - first_more;
       int lo = 0, hi = G;                     // invariant: pfx[lo] <= key < pfx[hi]
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (pfx[mid] <= key) lo = mid; else hi = mid;
+      if (key < UF) {
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (pfx_full[mid] <= key) lo = mid; else hi = mid;
+        }
+        split = 1 + key - pfx_full[lo];
+      } else {
+        key -= UF;
+        int c = 3;                            // longest class first
+        if (key >= UR3) { key -= UR3; c = 2; if (key >= UR2) { key -= UR2; c = 1; if (key >= UR1) { key -= UR1; c = 0; } } }
+        const unsigned short* pfx = pfx_rem[c];
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if ((int)pfx[mid] <= key) lo = mid; else hi = mid;
+        }
+        split = 1 + pfx_full[lo + 1] - pfx_full[lo];
       }
       // pfx[lo] <= key < pfx[lo + 1]: group lo owns the unit (groups without a unit of this kind repeat
       // their successor's prefix value and are never landed on)
       grp = lo;
-      split = is_full ? 1 + key - pfx_full[grp] : 1 + pfx_full[grp + 1] - pfx_full[grp];
     }
     decode_slice<ROWS128, B16>(p, smem, grp / p.Hkv, grp % p.Hkv, split);
     if (tid == 0)
