@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_split_mfma_kernel(DecodePa
 // that exist instead of one work-group per (group, slice of the list capacity), most of which would
 // find nothing to do and only hold a slot while they find out (a threshold selection may list every
 // block, so the capacity is the whole sequence).
-//   Round 0: work-group w takes the first slice of group w straight away, like the grid kernel would.
+//   First pass: work-group w takes the first slice of group w straight away, like the grid kernel would.
 //   Then every work-group derives the same table of the remaining units from the groups' counts:
 //     [0, G - W)   first slices of the groups W .. G-1 (when there are more groups than work-groups),
 //     then         the further slices of full length of all groups, in group order,
@@ -535,7 +535,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
         for (int c = 0; c < 4; ++c) ri[c] += xr[c];
       }
     }
-    __syncthreads();                          // round 0 is done with its LDS; wsum is free
+    __syncthreads();                          // the first pass is done with its LDS; wsum is free
     if (lane == 63) {
       wsum[0][wave] = fi;
 #pragma unroll
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(256, 2) void seer_decode_persist_mfma_kernel(Decode
     }
     __syncthreads();
   }
-  const int first_more = G > W ? G - W : 0;   // first slices that round 0 did not cover
+  const int first_more = G > W ? G - W : 0;   // first slices that the first pass did not cover
   const int UF = pfx_full[G];
   const int UR3 = pfx_rem[3][G], UR2 = pfx_rem[2][G], UR1 = pfx_rem[1][G], UR0 = pfx_rem[0][G];
   const int D = first_more + UF + UR3 + UR2 + UR1 + UR0;
