@@ -223,6 +223,11 @@ class Bench:
         ms_step = self.timed(self.step, steps, warmup)
         kern, step_ev = self.profiled(self.step, steps, warmup)
         ab, idx_cpu, cnt_cpu = self.selection()
+        # the decode call alone (split + merge launches), queued back to back on lists made beforehand: no
+        # event records between the kernels, which add 1-3 us to each short kernel's HIP-event figure
+        for r in range(self.R):
+            self.gate(r)
+        dec_b2b_us = self.timed(lambda i: self.decode(i % self.R, i % self.kv_copies), steps, warmup) * 1e3
         split, merge = kern["decode_split"], kern["decode_merge"]
         merge_mean = merge["mean"] if merge else 0.0
         dec_us = split["mean"] + merge_mean
@@ -241,7 +246,9 @@ class Bench:
                          "algorithmic_bytes_per_launch": ab["decode"], "avg_kernel_us": dec_us,
                          "split_kernel_us": split, "merge_kernel_us": merge,
                          "frac_split_kernel_alone": ab["decode"] / (split["mean"] * 1e-6) / 1e9 / HBM_PEAK_GBPS,
-                         "frac_at_min_duration": ab["decode"] / ((split["min"] + (merge["min"] if merge else 0.0)) * 1e-6) / 1e9 / HBM_PEAK_GBPS},
+                         "frac_at_min_duration": ab["decode"] / ((split["min"] + (merge["min"] if merge else 0.0)) * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                         "decode_call_us_back_to_back": dec_b2b_us,
+                         "frac_decode_calls_back_to_back": ab["decode"] / (dec_b2b_us * 1e-6) / 1e9 / HBM_PEAK_GBPS},
             "gate_roofline": {"bound": "hbm", "kernel": "seer_gate_score + seer_gate_select" if kern["gate_score"] else "seer_gate_select (fused: scores and selection)",
                               "achieved": ab["gate"] / (gate_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": ab["gate"] / (gate_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
@@ -511,7 +518,8 @@ def compact(res, b):
            "ms_per_step": res["ms_per_step"], "step_us_gpu_events": res["step_us"]["gpu_events"],
            "realised_sparsity": res["realised_sparsity"], "ragged_lists_hint": b.ragged,
            "roofline": {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic",
-                                          "algorithmic_bytes_per_launch", "avg_kernel_us", "frac_split_kernel_alone")},
+                                          "algorithmic_bytes_per_launch", "avg_kernel_us", "frac_split_kernel_alone",
+                                          "decode_call_us_back_to_back", "frac_decode_calls_back_to_back")},
            "gate_frac_hbm_peak": res["gate_roofline"]["frac"],
            "kernels_us": {k: ({"mean": v["mean"], "median": v["median"], "min": v["min"]} if v else None)
                           for k, v in res["kernels_us"].items()}}
