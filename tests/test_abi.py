@@ -175,6 +175,12 @@ def test_split_plan_properties_on_the_host():
         assert seer.decode_plan(16, 8, 13, 64)[0] == 1
         assert seer.decode_plan(16, 8, 64, 64)[0] == 2
         assert seer.decode_plan(1, 8, 256, 64)[0] == 32
+        # lists of very different lengths: slices of about 2048 tokens, shorter when the whole batch holds
+        # only a few slices per resident work-group
+        assert seer.decode_plan(128, 8, 203, 64, ragged=True) == (7, 29)
+        assert seer.decode_plan(128, 8, 2022, 64, ragged=True) == (64, 32)
+        assert seer.decode_plan(32, 8, 49, 128, ragged=True) == (7, 7)
+        assert seer.decode_plan(64, 8, 205, 64, ragged=True)[1] * 64 <= 2048
     finally:
         for knob in (0, 1, 3):
             seer.set_knob(knob, 0)
