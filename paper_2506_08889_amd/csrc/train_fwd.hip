@@ -13,8 +13,9 @@
 //                 and stored before the single barrier of the iteration); B = Q^T in registers.
 //   softmax       lane holds 4 keys x 2 tiles of one query row; causal mask on the diagonal chunks;
 //                 the chunk maximum doubles as the block maximum (running over the chunks of a block).
-//   O^T = V^T P^T B = P^T rounded to bf16, already in operand layout; A = V^T built in registers
-//                 from the work-group's V tile in LDS (8 rows x 16 bytes per lane, 16-bit interleaves).
+//   O^T = V^T P^T B = P^T rounded to bf16, already in operand layout; A = V^T straight from the
+//                 work-group's V tile in LDS through the transposing LDS read (ds_read_b64_tr_b16):
+//                 two reads of 4 keys each give a lane its 8 keys of one feature, no permutes.
 // K and V tiles are fetched by all 256 threads one iteration ahead, directly into the other LDS stage,
 // so a row crosses the memory system once per work-group and its latency is covered by a whole
 // iteration of arithmetic.
@@ -32,9 +33,6 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 namespace {
 
-__device__ __forceinline__ uint32_t tf_dword(const uint4& v, int i) {
-  return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
-}
 __device__ __forceinline__ uint32_t tf_pack_bf16(float a, float b) {
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   bf16x2_t r;
@@ -44,6 +42,9 @@ __device__ __forceinline__ uint32_t tf_pack_bf16(float a, float b) {
 }
 
 #define SEER_LDS_PTR(ptr) ((__attribute__((address_space(3))) void*)(ptr))
+#define SEER_LDS_PTR_T(type, ptr) ((__attribute__((address_space(3))) type*)(ptr))
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kQTile = 128;   // query rows per work-group
 constexpr int kKTile = 64;    // keys per iteration
@@ -121,7 +122,8 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
 
   // K / V tile staging.  Thread (srow = tid/16, schunk = tid%16) owns the 16-byte slot `schunk` of rows
   // 16*u + srow of a tile.  K rows are kept XOR-swizzled (slot s of row r holds chunk s ^ (r & 15):
-  // operand reads walk 16 rows at one chunk), V rows plainly (reads walk one row).  Whole tiles are
+  // operand reads walk 16 rows at one chunk), V rows swizzled in 32-byte units (slot s of row r holds
+  // chunk s ^ 2*(r & 7): the transposing operand reads walk 16 rows at one 32-byte column).  Whole tiles are
   // fetched straight into LDS (global_load_lds: a wave fills 1 KiB = its 4 rows, lane l at +16*l, so
   // the swizzle is applied to the global address); no staging registers, no LDS store instructions.
   // The last tile of a sequence whose length is not a multiple of 64 goes through registers with the
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
   const int srow = tid >> 4, schunk = tid & 15;
   const int wave_rows = __builtin_amdgcn_readfirstlane(wave) * 4;
   const uint16_t* kptr = kbase + (int64_t)srow * st + ((schunk ^ (srow & 15)) * 8);
-  const uint16_t* vptr = vbase + (int64_t)srow * st + schunk * 8;
+  const uint16_t* vptr = vbase + (int64_t)srow * st + ((schunk ^ ((srow & 7) << 1)) * 8);
   auto fetch_tile = [&](int kt0, unsigned char* kdst, unsigned char* vdst) {
     const uint16_t* kp = kptr + (int64_t)kt0 * st;
     const uint16_t* vp = vptr + (int64_t)kt0 * st;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
         }
         const int row = 16 * u + srow;
         *reinterpret_cast<uint4*>(kdst + row * 256 + (schunk << 4)) = kr;     // kr already is the swizzled chunk
-        *reinterpret_cast<uint4*>(vdst + row * 256 + (schunk << 4)) = vr;
+        *reinterpret_cast<uint4*>(vdst + row * 256 + (schunk << 4)) = vr;     // likewise
       }
     }
   };
@@ -264,25 +266,23 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
                                 tf_pack_bf16(pr[8 * c + 4], pr[8 * c + 5]), tf_pack_bf16(pr[8 * c + 6], pr[8 * c + 7]));
       }
 
-      // ---- O^T += V^T P^T per 32-key half: lane reads 8 keys x 16 bytes, key of slot j = tau(q4, j) =
-      //      j < 4 ? 4*q4 + j : 16 + 4*q4 + (j - 4), the order the probabilities sit in ----------------
+      // ---- O^T += V^T P^T per 32-key half and 16-feature tile e.  The A operand of lane (n16, q4) is
+      //      V[key tau(q4, j)][feature 16e + n16], j = 0..7, tau(q4, j) = j < 4 ? 4*q4 + j : 16 + 4*q4 + (j - 4)
+      //      (the order the probabilities sit in).  A transposing read hands lane n16 of a 16-lane group
+      //      element n16 % 4 of the 8-byte pieces addressed by lanes n16/4, n16/4 + 4, + 8, + 12 of the
+      //      group; so lane n16 addresses key 4*q4 + n16/4 (and that key + 16), features 16e + 4*(n16 % 4)
+      //      .. + 3, and receives four consecutive keys of feature 16e + n16 per read. -------------------
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        uint4 vr[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int row = 32 * c + ((j < 4) ? 4 * q4 + j : 16 + 4 * q4 + (j - 4));
-          vr[j] = *reinterpret_cast<const uint4*>(vt + row * 256 + (n16 << 4));
-        }
+        const int row0 = 32 * c + 4 * q4 + (n16 >> 2);                   // the key this lane addresses (and row0 + 16)
+        const int sw = (row0 & 7) << 1;                                  // (row0 + 16) & 7 == row0 & 7
+        const unsigned char* vrow = vt + row0 * 256 + ((n16 & 1) << 3);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          uint32_t o[4];
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const uint32_t x0 = tf_dword(vr[2 * jj], e >> 1), x1 = tf_dword(vr[2 * jj + 1], e >> 1);
-            o[jj] = __builtin_amdgcn_perm(x1, x0, (e & 1) ? 0x07060302u : 0x05040100u);
-          }
-          const uint4 va = make_uint4(o[0], o[1], o[2], o[3]);
+          const int slot = (2 * e + ((n16 & 3) >> 1)) ^ sw;              // 16-byte slot that holds the piece
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SEER_LDS_PTR_T(s16x4_t, vrow + (slot << 4)));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SEER_LDS_PTR_T(s16x4_t, vrow + 16 * 256 + (slot << 4)));
+          const s16x8_t va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
           for (int a = 0; a < 2; ++a)
             oacc[a][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va),
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
     if (it + 1 < ntiles) iteration(it + 1, kbuf_b, vbuf_b, kbuf_a, vbuf_a);
   }
 
-  // ---- results: lane (n16, q4) holds O[row n16 of tile a][32*q4 + 8*r + e] in oacc[a][e][r] ---------
+  // ---- results: lane (n16, q4) holds O[row n16 of tile a][16*e + 4*q4 + r] in oacc[a][e][r] ---------
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
     float l = l_run[a];
@@ -321,20 +321,15 @@ __global__ __launch_bounds__(256, 2) void seer_attn_fwd_kernel(TrainFwdParams p)
     const float inv = (real && l > 0.f) ? 1.0f / l : 0.f;
     const int64_t orow = ((int64_t)i * p.T + row) * p.Hq + h;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int c0 = 32 * q4 + 8 * r;
+    for (int e = 0; e < 8; ++e) {
+      const int c0 = 16 * e + 4 * q4;
       if (p.out_is_f32) {
-        float* dst = reinterpret_cast<float*>(p.out) + orow * kHeadDim + c0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dst[e] = oacc[a][e][r] * inv;
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + orow * kHeadDim + c0) =
+            make_float4(oacc[a][e][0] * inv, oacc[a][e][1] * inv, oacc[a][e][2] * inv, oacc[a][e][3] * inv);
       } else {
-        uint32_t w[4];
-#pragma unroll
-        for (int e = 0; e < 8; e += 2)
-          w[e >> 1] = (uint32_t)f32_to_bf16_rne(oacc[a][e][r] * inv) |
-                      ((uint32_t)f32_to_bf16_rne(oacc[a][e + 1][r] * inv) << 16);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(p.out) + orow * kHeadDim + c0) =
-            make_uint4(w[0], w[1], w[2], w[3]);
+        const uint32_t w0 = (uint32_t)f32_to_bf16_rne(oacc[a][e][0] * inv) | ((uint32_t)f32_to_bf16_rne(oacc[a][e][1] * inv) << 16);
+        const uint32_t w1 = (uint32_t)f32_to_bf16_rne(oacc[a][e][2] * inv) | ((uint32_t)f32_to_bf16_rne(oacc[a][e][3] * inv) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(p.out) + orow * kHeadDim + c0) = make_uint2(w0, w1);
       }
     }
     if (q4 == 0) {
