@@ -349,7 +349,7 @@ def main_workload(args, seer, synth, torch, np):
 
     # ---- several new tokens per call (multi-token / speculative decoding): same bytes, q_len x the tokens
     multi = None
-    if 16 // w.g >= 2 and bs % 32 == 0:
+    if 16 // w.g >= 2 and bs % 32 == 0 and args.impl != 1:      # the matrix-core kernel only
         T = min(16 // w.g, 4)
         qm = synth.randn_bf16((B, T, Hq, d), dev, synth.generator(dev, w.seed + 3000))
         out_m = torch.empty(B, T, Hq, d, dtype=torch.bfloat16, device=dev)
