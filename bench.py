@@ -713,8 +713,8 @@ def paper_sweep(args, seer, synth, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--rotate", type=int, default=4, help="independent query sets cycled through the steps")
     ap.add_argument("--kv-copies", type=int, default=0, help="independent KV caches cycled (0 = auto)")
