@@ -580,6 +580,18 @@ def test_gate_very_long_cache_and_crowded_boundary():
         gi, gc = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, mode=mode, **kw)
         torch.cuda.synchronize()
         check_indices(gi, gc, ri, rc, what=f"8300-block cache mode={mode}")
+    # (a') 20 000 blocks of small-integer data (many equal scores): the ordered compaction runs three passes of
+    # 8192 blocks and the radix walk settles ties that straddle the passes
+    nb3 = 20000
+    gnp = np.random.default_rng(92)
+    qg3 = torch.from_numpy(gnp.integers(-2, 3, size=(1, 2, 128)).astype(np.float32)).to(torch.bfloat16)
+    kc3 = torch.from_numpy(gnp.integers(-1, 2, size=(1, 2, nb3, 128)).astype(np.float32)).to(torch.bfloat16)
+    sl3 = torch.tensor([nb3 * bs - 5], dtype=torch.int32)
+    for k in (1, 6000, 19999):
+        ri, rc = oracle.gate_select(qg3, kc3, sl3, bs, budget_tokens=k * bs, max_sel=k)
+        gi, gc = seer.gate_select(qg3.to(DEV), kc3.to(DEV), sl3.to(DEV), bs, budget_tokens=k * bs, max_sel=k)
+        torch.cuda.synchronize()
+        check_indices(gi, gc, ri, rc, what=f"20000-block cache k={k}")
     # (b) 900 of 1000 blocks share one score, the k-th largest falls among them
     nb2 = 1000
     kc2 = torch.randn(1, 2, nb2, 128, generator=gen).to(torch.bfloat16)
