@@ -605,6 +605,50 @@ def test_gate_very_long_cache_and_crowded_boundary():
         check_indices(gi, gc, ri, rc, what=f"crowded boundary k={budget_blocks}")
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_gate_random_shapes_with_many_equal_scores(seed):
+    """Token-budget selection on 60 random shapes per seed: batch 1-4, 1-3 kv heads, every block size, caches
+    from 1 to 3000 blocks (and the sizes around the kernel's 256 / 512 / 1024 / 8192 steps), sequence
+    lengths from empty to full, global and per-sequence budgets from nothing to everything; inputs of small
+    integers, constant rows or a handful of distinct rows, so that equal scores are the rule and the
+    lowest-index rule decides most lists.  Both gate forms, bit-exact against the oracle."""
+    rng = np.random.default_rng(seed)
+    for case in range(60):
+        B, Hkv, bs = int(rng.integers(1, 5)), int(rng.integers(1, 4)), int(rng.choice([16, 32, 64, 128]))
+        nb_max = int(rng.choice([1, 2, 3, 5, 17, 64, 100, 255, 256, 257, 511, 512, 513, 700, 1024, 1500, 2048, 2500, 3000, 8192, 8200]))
+        if rng.random() < 0.3:
+            nb_max = int(rng.integers(1, 3001))
+        seqlens = rng.integers(0, nb_max * bs + 1, size=B).astype(np.int32)
+        seqlens[rng.integers(0, B)] = nb_max * bs - int(rng.integers(0, bs))      # one nearly full sequence
+        kind = rng.choice(["ties", "normal", "const", "few"])
+        if kind == "ties":
+            q = rng.integers(-2, 3, size=(B, Hkv, 128)).astype(np.float32)
+            kc = rng.integers(-1, 2, size=(B, Hkv, nb_max, 128)).astype(np.float32)
+        elif kind == "const":
+            q, kc = np.ones((B, Hkv, 128), np.float32), np.ones((B, Hkv, nb_max, 128), np.float32)
+        elif kind == "few":
+            q = rng.standard_normal((B, Hkv, 128)).astype(np.float32)
+            kc = rng.standard_normal((4, 128)).astype(np.float32)[rng.integers(0, 4, size=(B, Hkv, nb_max))]
+        else:
+            q = rng.standard_normal((B, Hkv, 128)).astype(np.float32)
+            kc = rng.standard_normal((B, Hkv, nb_max, 128)).astype(np.float32)
+        qg, kct, sl = torch.from_numpy(q).to(torch.bfloat16), torch.from_numpy(kc).to(torch.bfloat16), torch.from_numpy(seqlens)
+        if rng.random() < 0.5:
+            bb, bt = None, int(rng.integers(0, nb_max * bs + 1))
+            k = min(-(-bt // bs), nb_max)
+        else:
+            bbn = rng.integers(0, nb_max + 2, size=B).astype(np.int32)
+            bb, bt, k = torch.from_numpy(bbn), 0, int(min(bbn.max(), nb_max))
+        max_sel = max(1, k)
+        ri, rc = oracle.gate_select(qg, kct, sl, bs, budget_tokens=bt, budget_blocks=bb, max_sel=max_sel)
+        gi, gc = gate_both_impls(qg.to(DEV), kct.to(DEV), sl.to(DEV), bs, budget_tokens=bt,
+                                 budget_blocks=None if bb is None else bb.to(DEV), max_sel=max_sel,
+                                 ragged=bool(rng.random() < 0.5))
+        check_indices(gi, gc, ri, rc, what=f"seed {seed} case {case}: {kind} B={B} Hkv={Hkv} bs={bs} nb_max={nb_max} "
+                                            f"budget_tokens={bt} budget_blocks={None if bb is None else bb.tolist()} "
+                                            f"seqlens={seqlens.tolist()}")
+
+
 @pytest.mark.parametrize("nb_max", [6144, 8192])
 def test_gate_cache_lengths_whose_scores_need_more_than_64k_of_lds(nb_max):
     """6144 and 8192 blocks (16-token blocks on 96 k / 128 k tokens): the select kernel's LDS copy of the
@@ -716,6 +760,38 @@ def test_ragged_lists_hint_hand_out_of_slices(B, Hkv, smax):
                                  page_size=inp.page_size, out_dtype=torch.float32, ragged=True)
     torch.cuda.synchronize()
     check_decode(out, lse, dref_out, dref_lse, tight=True, what=f"ragged dense B={B}")
+
+
+def test_ragged_lists_hint_on_random_shapes():
+    """The slice hand-out on 16 random shapes: 1-8 kv heads, groups of 1-8 heads, every block size, batches
+    from 1 to 300 sequences of log-uniform lengths (paged or not), lists from empty to everything in random
+    order, a workspace of arbitrary bytes; fp32 output at the tight bars, and a second call on the same
+    workspace (hand-out word now valid) must reproduce the first bit for bit."""
+    rng = np.random.default_rng(2024)
+    for case in range(16):
+        Hkv, g, bs = int(rng.choice([1, 2, 3, 8])), int(rng.integers(1, 9)), int(rng.choice([16, 32, 64, 128]))
+        B = int(rng.choice([1, 2, 5, 17, 40, 70, 300])) if Hkv < 8 else int(rng.choice([1, 3, 20, 64, 257]))
+        smax = int(rng.choice([bs * 40, bs * 150, 2048 * 6 + 5, 2048 * 20 + 77]))
+        smax = max(2, min(smax, 200000 // max(1, B // 8)))
+        w = synth.Workload("rr", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen_range=(1, smax), seqlen_dist="loguniform",
+                           paged=bool(rng.random() < 0.5), budget_tokens=0, budget_frac=0.5, seed=int(rng.integers(1, 1 << 30)))
+        inp = synth.make_inputs(w, DEV)
+        nb = (inp.seqlens_cpu + bs - 1) // bs
+        k_sel = [int(rng.integers(0, int(n) + 1)) for n in nb]
+        idx, cnt = synth.random_block_lists(B, Hkv, nb, k_sel, inp.nb_max, torch.Generator().manual_seed(case),
+                                            ascending=bool(rng.random() < 0.5))
+        ref_out, ref_lse = oracle_decode(inp, idx, cnt)
+        ws = torch.randint(0, 256, (seer.decode_workspace_bytes(B, w.Hq, Hkv, w.d, inp.nb_max),), dtype=torch.uint8, device=DEV)
+        res = []
+        for rep in range(2):
+            out, lse = seer.sparse_decode(inp.q, inp.k, inp.v, inp.seqlens, idx.to(DEV), cnt.to(DEV), bs, w.scale,
+                                          page_table=inp.page_table, page_size=inp.page_size, out_dtype=torch.float32,
+                                          workspace=ws, ragged=True)
+            torch.cuda.synchronize()
+            check_decode(out, lse, ref_out, ref_lse, tight=True,
+                         what=f"case {case}: B={B} Hkv={Hkv} g={g} bs={bs} smax={smax} paged={w.paged} call {rep}")
+            res.append((out.clone(), lse.clone()))
+        assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1]), f"case {case}: the second call differs"
 
 
 def test_bursts_and_overlapping_streams():
