@@ -239,6 +239,8 @@ class Bench:
                         "kernels_only_mean": sum(v["mean"] for v in kern.values() if v)},
             "kernels_us": kern,
             "realised_sparsity": ab["sparsity"],
+            # (token, kv head) pairs of the selected blocks read per second of the whole step
+            "selected_kv_tokens_per_s": ab["selected_tokens"] / (ms_step * 1e-3),
             "roofline": {"bound": "hbm",
                          "kernel": "seer_decode_split (sparse)" + (" + seer_decode_merge" if merge else ""),
                          "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
@@ -425,6 +427,7 @@ def main_workload(args, seer, synth, torch, np):
         "roofline": roof,
         "gate_roofline": res["gate_roofline"],
         "hbm_GBps_selected_kv": roof["achieved"], "pct_hbm_peak": 100.0 * roof["frac"],
+        "selected_kv_tokens_per_s": res["selected_kv_tokens_per_s"],
         "step_us": res["step_us"],
         "kernels_us": res["kernels_us"],
         "stream_read_GBps": stream_gbps,
@@ -516,7 +519,8 @@ def compact(res, b):
     r = res["roofline"]
     out = {"workload": b.describe(), "value": b.w.B / (res["ms_per_step"] * 1e-3), "unit": "tokens/s",
            "ms_per_step": res["ms_per_step"], "step_us_gpu_events": res["step_us"]["gpu_events"],
-           "realised_sparsity": res["realised_sparsity"], "ragged_lists_hint": b.ragged,
+           "realised_sparsity": res["realised_sparsity"], "selected_kv_tokens_per_s": res["selected_kv_tokens_per_s"],
+           "ragged_lists_hint": b.ragged,
            "roofline": {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic",
                                           "algorithmic_bytes_per_launch", "avg_kernel_us", "frac_split_kernel_alone",
                                           "decode_call_us_back_to_back", "frac_decode_calls_back_to_back")},
