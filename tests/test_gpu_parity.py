@@ -794,6 +794,80 @@ def test_ragged_lists_hint_on_random_shapes():
         assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1]), f"case {case}: the second call differs"
 
 
+def test_multi_token_decode_on_random_shapes():
+    """q_len new tokens per call on 24 random shapes: group sizes 1-8 with every q_len the 16-row tile
+    allows, blocks of 32/64/128 tokens, contiguous and paged caches of log-uniform lengths, lists from
+    empty to everything (mostly with the last block, where the causal limits among the new tokens bite),
+    forced split counts and the ragged-lists hint; fp32 output at the tight bars."""
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        Hkv, g, bs = int(rng.choice([1, 2, 3, 8])), int(rng.integers(1, 9)), int(rng.choice([32, 64, 128]))
+        T = int(rng.integers(1, 16 // g + 1))
+        B = int(rng.choice([1, 2, 5, 17, 33]))
+        smax = int(rng.choice([bs * 10, bs * 40 + 7, 2048 * 3 + 5]))
+        paged = bool(rng.random() < 0.5)
+        w = synth.Workload("mtr", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen_range=(1, smax), seqlen_dist="loguniform",
+                           paged=paged, budget_tokens=0, budget_frac=0.5, seed=int(rng.integers(1, 1 << 30)))
+        inp = synth.make_inputs(w, DEV)
+        nb = (inp.seqlens_cpu + bs - 1) // bs
+        gen = torch.Generator().manual_seed(case)
+        idx, cnt = synth.random_block_lists(B, Hkv, nb, [int(rng.integers(0, int(n) + 1)) for n in nb], inp.nb_max, gen,
+                                            ascending=bool(rng.random() < 0.5))
+        for i in range(B):
+            if rng.random() < 0.7:
+                for h in range(Hkv):
+                    c = int(cnt[i, h])
+                    if c > 0 and (idx[i, h, :c] == int(nb[i]) - 1).sum() == 0:
+                        idx[i, h, 0] = int(nb[i]) - 1
+        qm = torch.randn(B, T, g * Hkv, 128, generator=gen).to(torch.bfloat16)
+        kv = oracle.KVLayout(cpu(inp.k), cpu(inp.v), cpu(inp.page_table) if paged else None, inp.page_size if paged else 0)
+        ref_out, ref_lse = oracle.sparse_decode_multi(qm, kv, inp.seqlens_cpu, idx, cnt, bs, w.scale)
+        ragged, ns = bool(rng.random() < 0.5), int(rng.choice([0, 0, 1, 2, 3, 5]))
+        seer.set_knob(1, ns)
+        out, lse = seer.sparse_decode_multi(qm.to(DEV), inp.k, inp.v, inp.seqlens, idx.to(DEV), cnt.to(DEV), bs, w.scale,
+                                            page_table=inp.page_table, page_size=inp.page_size, out_dtype=torch.float32,
+                                            ragged=ragged)
+        torch.cuda.synchronize()
+        seer.set_knob(1, 0)
+        R = T * g * Hkv
+        check_decode(out.view(B, R, 128), lse.view(B, R), np.asarray(ref_out).reshape(B, R, 128),
+                     np.asarray(ref_lse).reshape(B, R), tight=True,
+                     what=f"case {case}: B={B} Hkv={Hkv} g={g} T={T} bs={bs} smax={smax} paged={paged} ragged={ragged} ns={ns}")
+
+
+@pytest.mark.parametrize("seed", [5, 6])
+def test_threshold_and_top_p_on_random_shapes(seed):
+    """Threshold and top-p selection on 30 random shapes per seed (1-4 sequences of random lengths, 1-3 kv
+    heads, every block size, caches of 3 to 3000 blocks, logits of three spreads), the threshold / the mass
+    placed in the widest gap near a random target, both gate forms: indices bit-exact against the oracle."""
+    rng = np.random.default_rng(seed)
+    for case in range(30):
+        B, Hkv, bs = int(rng.integers(1, 5)), int(rng.integers(1, 4)), int(rng.choice([16, 32, 64, 128]))
+        nb_max = int(rng.choice([3, 5, 17, 64, 100, 255, 256, 257, 511, 512, 513, 700, 1024, 1500, 2048, 2500, 3000]))
+        seqlens = rng.integers(2 * bs, nb_max * bs + 1, size=B).astype(np.int32)
+        seqlens[rng.integers(0, B)] = nb_max * bs - int(rng.integers(0, bs))
+        amp = float(rng.choice([0.3, 1.0, 3.0]))
+        qg = torch.from_numpy((amp * rng.standard_normal((B, Hkv, 128))).astype(np.float32)).to(torch.bfloat16)
+        kc = torch.from_numpy(rng.standard_normal((B, Hkv, nb_max, 128)).astype(np.float32)).to(torch.bfloat16)
+        sl = torch.from_numpy(seqlens)
+        _, _, scores = oracle.gate_select(qg, kc, sl, bs, budget_tokens=bs, max_sel=nb_max, return_scores=True)
+        scores = np.asarray(scores)
+        for mode in (oracle.SELECT_THRESHOLD, oracle.SELECT_TOPP):
+            if mode == oracle.SELECT_THRESHOLD:
+                thr = pick_threshold(scores, seqlens, bs, 128, float(rng.choice([0.05, 0.1, 0.3, 0.6])))
+            else:
+                thr = pick_top_p(scores, seqlens, bs, 128, 0.2, 0.95, seed=case)
+            ref_idx, ref_cnt = oracle.gate_select(qg, kc, sl, bs, mode=mode, threshold=thr, max_sel=nb_max)
+            for impl in (1, 2):
+                seer.set_knob(3, impl)
+                idx, cnt = seer.gate_select(qg.to(DEV), kc.to(DEV), sl.to(DEV), bs, mode=mode, threshold=thr, max_sel=nb_max,
+                                            ragged=bool(rng.random() < 0.5))
+                torch.cuda.synchronize()
+                seer.set_knob(3, 0)
+                check_indices(idx, cnt, ref_idx, ref_cnt,
+                              what=f"case {case} mode {mode} gate form {impl}: B={B} Hkv={Hkv} bs={bs} nb_max={nb_max} thr={thr}")
+
+
 def test_bursts_and_overlapping_streams():
     """200 back-to-back calls without a synchronisation, then calls overlapping on two streams (each
     with its own query set, outputs and workspace): results identical to the same calls made alone.
