@@ -176,3 +176,44 @@ def test_front_end_to_decode_chain():
     check_decode(out, lse, ro, rl, tight=True, what="chain decode")
     # the partial last block (9 tokens) is selected although it has no cache entry
     assert (idx.cpu()[:, :, :].max(dim=2).values == 70).all()
+
+
+def test_front_end_on_random_shapes():
+    """Q branch, K branch and the one-call form on 20 random shapes: 1-8 kv heads, groups of 1-8 heads,
+    batches around the 16-sequence tile, every block size, contiguous and paged caches, sequences from
+    empty to 60 blocks.  Entries of blocks that are not full must stay untouched."""
+    rng = np.random.default_rng(2025)
+    for case in range(20):
+        Hkv, g, B = int(rng.choice([1, 2, 3, 8])), int(rng.integers(1, 9)), int(rng.choice([1, 2, 15, 16, 17, 33, 70]))
+        bs, paged = int(rng.choice([16, 32, 64, 128])), bool(rng.random() < 0.5)
+        hi = int(rng.choice([bs * 2, bs * 20 + 5, bs * 60 + 1]))
+        w = synth.Workload("fr", B=B, Hq=g * Hkv, Hkv=Hkv, block_size=bs, seqlen_range=(1, hi), seqlen_dist="uniform",
+                           paged=paged, budget_tokens=bs * 3, seed=int(rng.integers(1, 1 << 30)))
+        inp = synth.make_inputs(w, DEV)
+        wq, wk = synth.gate_weights(w, DEV, synth.generator(DEV, case + 1))
+        cos, sin = synth.rope_tables(inp.nb_max * bs + 1, w.Dg, device=DEV)
+        sl = inp.seqlens_cpu.clone()
+        if rng.random() < 0.3:
+            sl[int(rng.integers(0, B))] = 0
+        sld = sl.to(DEV)
+        what = f"case {case}: B={B} Hkv={Hkv} g={g} bs={bs} paged={paged}"
+        got = seer.gate_q(inp.q, wq, cos, sin, sld)
+        torch.cuda.synchronize()
+        ref, bits = oracle.gate_q(inp.q.cpu(), wq.cpu(), cos.cpu(), sin.cpu(), sl)
+        bf16_close(got, ref, bits, what + " gate_q")
+        kc = torch.full((B, Hkv, inp.nb_max, w.Dg), 7.0, dtype=torch.bfloat16, device=DEV)
+        seer.kc_update(inp.k, wk, cos, sin, sld, bs, kc, page_table=inp.page_table, page_size=inp.page_size)
+        torch.cuda.synchronize()
+        refk, bitsk = oracle.kc_update(cpu(inp.k), wk.cpu(), cos.cpu(), sin.cpu(), sl, bs, inp.nb_max,
+                                       page_table=cpu(inp.page_table), page_size=inp.page_size)
+        if (~np.isnan(refk)).any():
+            bf16_close(kc, refk, bitsk, what + " kc_update")
+        assert (kc.float().cpu().numpy()[np.isnan(refk)] == 7.0).all(), what + ": kc_update touched an entry it must not"
+        # one call from the raw queries: the same gate query, and the oracle's selection given that query
+        qg_out = torch.empty(B, Hkv, w.Dg, dtype=torch.bfloat16, device=DEV)
+        kcz = torch.where(torch.isnan(torch.from_numpy(refk).to(DEV).float()), torch.zeros_like(kc), kc)
+        idx, cnt = seer.gate_select_q(inp.q, wq, cos, sin, kcz, sld, bs, budget_tokens=bs * 3, max_sel=3, q_gate=qg_out)
+        torch.cuda.synchronize()
+        assert torch.equal(qg_out, got), what + ": the gate query of the one-call form differs"
+        ridx, rcnt = oracle.gate_select(qg_out.cpu(), kcz.cpu(), sl, bs, budget_tokens=bs * 3, max_sel=3)
+        check_indices(idx, cnt, ridx, rcnt, what=what + " gate_select_q")
